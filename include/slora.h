@@ -1,0 +1,135 @@
+/* slora.h -- C ABI of the MI355X (gfx950) library for the server-side step of split
+ * federated LoRA fine-tuning (SplitLoRA, arXiv 2407.00952).
+ *
+ * What the calls compute (paper passages):
+ *   Sec. II-C       LoRA: a frozen weight W plus a trainable rank-r product.  Here
+ *                   y = x W^T + b + s (x A^T) B^T with A [r,in], B [out,r], s = alpha/r.
+ *   Sec. III-B a3   the central server concatenates the clients' cut-layer activations
+ *                   S = [s_1; ...; s_N] and runs the server-side model forward (Eq. 3),
+ *                   then back-propagates to obtain the gradients of the server adapters
+ *                   only (frozen weights get none) and updates them by SGD (Eq. 4, 5).
+ *   Sec. III-B a4   the activation gradient of each client's slice of S is returned.
+ *   Sec. III-B b2   client adapters are averaged with weights |D_i|/|D| (Eq. 8, 9).
+ * The server-side model is a stack of GPT-2 blocks (pre-LayerNorm, causal attention with
+ * head size 64, tanh-GELU MLP, biases on every linear); the loss head is the caller's:
+ * the backward call takes the gradient dY of the caller's loss w.r.t. the stack output.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with h_ (then HOST).
+ *   - The library never allocates or frees device memory, never synchronises the stream
+ *     and never writes to stdout.  `stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).  All work is queued on that stream; buffers must stay alive until
+ *     it has run.  Outputs must not alias inputs.
+ *   - Return value: 0 (SLORA_OK) or a negative SLORA_E* code.  All argument and state
+ *     checks happen before the first kernel launch, so they work on a machine without a GPU.
+ *   - A context is not thread-safe; use one per host thread / stream.
+ *   - Matrices are row-major, dense.  "bf16" is the upper 16 bits of an IEEE binary32.
+ */
+#ifndef SLORA_H
+#define SLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SLORA_OK        0
+#define SLORA_EINVAL   -1   /* NULL pointer, size out of range, unsupported configuration     */
+#define SLORA_ESTATE   -2   /* call order violated, or weights / adapters / workspace unbound */
+#define SLORA_ENOSPC   -3   /* workspace smaller than slora_workspace_bytes()                 */
+#define SLORA_EHIP     -4   /* a HIP call failed (text: slora_last_hip_error)                 */
+#define SLORA_EZERO    -5   /* FedAvg: negative sample count or zero total                    */
+
+/* projections that may carry an adapter; bit (1u << SLORA_PROJ_x) in lora_mask */
+enum { SLORA_PROJ_Q = 0, SLORA_PROJ_K = 1, SLORA_PROJ_V = 2, SLORA_PROJ_O = 3,
+       SLORA_PROJ_FC = 4, SLORA_PROJ_PR = 5, SLORA_NPROJ = 6 };
+
+/* frozen tensors of one block, all bf16 */
+enum { SLORA_LN1_G = 0, SLORA_LN1_B, SLORA_WQKV /* [3d,d]: rows q, then k, then v */, SLORA_BQKV /* [3d] */,
+       SLORA_WO /* [d,d] */, SLORA_BO, SLORA_LN2_G, SLORA_LN2_B, SLORA_WFC /* [d_ff,d] */, SLORA_BFC,
+       SLORA_WPR /* [d,d_ff] */, SLORA_BPR, SLORA_NFROZEN };
+
+#define SLORA_DTYPE_F32  0
+#define SLORA_DTYPE_BF16 1   /* bf16 storage, fp32 accumulation */
+
+#define SLORA_MAX_RANK    16
+#define SLORA_MAX_CLIENTS 64
+
+typedef struct slora_ctx slora_ctx;      /* opaque, host memory */
+
+typedef struct {
+    int32_t  d_model;      /* multiple of 64; head size d_model / n_head must be 64            */
+    int32_t  n_head;
+    int32_t  d_ff;         /* multiple of 64                                                   */
+    int32_t  n_blocks;     /* server-side blocks only                                          */
+    int32_t  lora_r;       /* 1 .. SLORA_MAX_RANK                                              */
+    float    lora_alpha;   /* s = lora_alpha / lora_r                                          */
+    uint32_t lora_mask;    /* which projections carry an adapter, same in every block          */
+    int32_t  dtype;        /* SLORA_DTYPE_BF16 (the stack has no fp32 variant)                 */
+    float    ln_eps;       /* e.g. 1e-5                                                        */
+    int32_t  max_seqs;     /* upper bound on the number of sequences per round (sum of b_i)    */
+    int32_t  seq_len;      /* S, multiple of 64, every sequence has exactly this length        */
+} slora_config;
+
+/* ---- context (host only) ---------------------------------------------------------------- */
+int    slora_create(const slora_config *cfg, slora_ctx **out);
+int    slora_destroy(slora_ctx *ctx);
+/* bytes of caller-owned device memory the context needs: transposed copies of the frozen
+ * weights, bf16 copies of the adapters, the activations saved between forward and backward,
+ * and scratch.  0 if ctx is NULL. */
+size_t slora_workspace_bytes(const slora_ctx *ctx);
+/* ws must be 256-byte aligned and stay alive while the context is used. */
+int    slora_bind_workspace(slora_ctx *ctx, void *ws, size_t bytes);
+/* Borrow one frozen tensor (bf16, shapes above) of block `block`; never written.  The next
+ * forward call queues the (one-off) transposed copies used by the backward pass. */
+int    slora_bind_frozen(slora_ctx *ctx, int block, int which, const void *w);
+/* Borrow the fp32 master adapter of projection `proj` in block `block`: A [r,in], B [out,r],
+ * and the gradient buffers dA [r,in], dB [out,r].  A, B are changed only by
+ * slora_adapter_step; dA, dB are overwritten by every slora_server_bwd. */
+int    slora_bind_adapter(slora_ctx *ctx, int block, int proj, float *A, float *B, float *dA, float *dB);
+
+/* ---- the round (Sec. III-B a3, a4): state machine  fwd -> bwd -> step ------------------------ */
+/* Forward of the concatenated activations (Eq. 3).  h_x_clients: K device pointers, client i
+ * holding [h_batch[i], S, d] bf16; y: [sum_i h_batch[i], S, d] bf16, clients in index order.
+ * Uses the adapters as they are now (R_s^{t-1}). */
+int slora_server_fwd(slora_ctx *ctx, int K, const void *const *h_x_clients, const int32_t *h_batch,
+                     void *y, void *stream);
+/* Backward of the forward just run.  dy: [sum b_i, S, d] bf16, gradient of the caller's loss
+ * w.r.t. y (any normalisation or client weighting is already inside dy).  Writes client i's
+ * activation gradient [b_i,S,d] bf16 to h_dx_clients[i] and, into every bound dA/dB, the sum
+ * over all tokens of all clients.  Never forms a weight, bias or LayerNorm gradient. */
+int slora_server_bwd(slora_ctx *ctx, const void *dy, void *const *h_dx_clients, void *stream);
+/* Eq. (4),(5): p = fmaf(-lr, g, p) on every bound A, B; legal only after a backward. */
+int slora_adapter_step(slora_ctx *ctx, float lr, void *stream);
+
+/* ---- client-adapter aggregation (Sec. III-B b2, Eq. 8-9) -------------------------------------- */
+/* out[j] = sum_i w_i x_i[j] over K flat fp32 vectors of n floats, with
+ * w_i = (float)((double)n_i / (double)sum n) and the fixed evaluation order
+ * acc = 0; for i = 0..K-1: acc = fmaf(w_i, x_i[j], acc)  -- bit-reproducible.
+ * K <= SLORA_MAX_CLIENTS; SLORA_EZERO if a count is negative or the total is zero. */
+int slora_fedavg(int K, const float *const *h_client_params, const int64_t *h_sample_counts,
+                 size_t n, float *out, void *stream);
+
+/* ---- one LoRA-adapted linear layer (Sec. II-C), used on its own -------------------------------- */
+/* y [T,out] = x [T,in] W[out,in]^T + bias + (alpha/r) (x A^T) B^T.  dtype F32: every buffer fp32.
+ * dtype BF16: x, W, bias, y bf16 and A, B fp32; `ws` is scratch of slora_lora_linear_ws_bytes().
+ * bias may be NULL.  r in 1..SLORA_MAX_RANK; in, out multiples of 64 for BF16. */
+size_t slora_lora_linear_ws_bytes(int dtype, int T, int n_in, int n_out, int r);
+int slora_lora_linear_fwd(int dtype, int T, int n_in, int n_out, int r, float alpha,
+                          const void *x, const void *W, const void *bias, const float *A, const float *B,
+                          void *y, void *ws, size_t ws_bytes, void *stream);
+/* dx [T,in] = dy W + s (dy B) A;  dA [r,in] = s (dy B)^T x;  dB [out,r] = s dy^T (x A^T).
+ * dtype as above (dx follows x's type, dA and dB are fp32). */
+int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float alpha,
+                          const void *x, const void *dy, const void *W, const float *A, const float *B,
+                          void *dx, float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
+
+const char *slora_strerror(int code);
+const char *slora_last_hip_error(void);   /* text of the last failed HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLORA_H */

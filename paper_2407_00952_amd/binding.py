@@ -1,0 +1,240 @@
+"""ctypes binding of libslora.so -- argument marshalling only.
+
+Every function has the name and argument order of its C declaration in include/slora.h
+(the paper passages each call implements are cited there).  PyTorch is used for device
+memory and the stream handle; no step of the method runs in Python or in torch ops.
+There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libslora.so")
+
+SLORA_OK, SLORA_EINVAL, SLORA_ESTATE, SLORA_ENOSPC, SLORA_EHIP, SLORA_EZERO = 0, -1, -2, -3, -4, -5
+PROJ = {"q": 0, "k": 1, "v": 2, "o": 3, "fc": 4, "pr": 5}
+FROZEN = {"ln1_g": 0, "ln1_b": 1, "Wqkv": 2, "bqkv": 3, "Wo": 4, "bo": 5, "ln2_g": 6, "ln2_b": 7,
+          "Wfc": 8, "bfc": 9, "Wpr": 10, "bpr": 11}
+DTYPE_F32, DTYPE_BF16 = 0, 1
+MAX_RANK, MAX_CLIENTS = 16, 64
+
+EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind_workspace",
+           "slora_bind_frozen", "slora_bind_adapter", "slora_server_fwd", "slora_server_bwd",
+           "slora_adapter_step", "slora_fedavg", "slora_lora_linear_ws_bytes", "slora_lora_linear_fwd",
+           "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error"]
+
+
+class slora_config(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("n_head", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("n_blocks", ctypes.c_int32), ("lora_r", ctypes.c_int32), ("lora_alpha", ctypes.c_float),
+                ("lora_mask", ctypes.c_uint32), ("dtype", ctypes.c_int32), ("ln_eps", ctypes.c_float),
+                ("max_seqs", ctypes.c_int32), ("seq_len", ctypes.c_int32)]
+
+
+class SloraError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libslora error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libslora.so (built by paper_2407_00952_amd.build); raises OSError if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("libslora.so not built: run `python -m paper_2407_00952_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.slora_create.argtypes = [ctypes.POINTER(slora_config), ctypes.POINTER(vp)]
+        L.slora_destroy.argtypes = [vp]
+        L.slora_workspace_bytes.argtypes = [vp]
+        L.slora_workspace_bytes.restype = sz
+        L.slora_bind_workspace.argtypes = [vp, vp, sz]
+        L.slora_bind_frozen.argtypes = [vp, i32, i32, vp]
+        L.slora_bind_adapter.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.slora_server_fwd.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.slora_server_bwd.argtypes = [vp, vp, vp, vp]
+        L.slora_adapter_step.argtypes = [vp, f32, vp]
+        L.slora_fedavg.argtypes = [i32, vp, vp, sz, vp, vp]
+        L.slora_lora_linear_ws_bytes.argtypes = [i32] * 5
+        L.slora_lora_linear_ws_bytes.restype = sz
+        L.slora_lora_linear_fwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slora_lora_linear_bwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slora_strerror.argtypes = [i32]
+        L.slora_strerror.restype = ctypes.c_char_p
+        L.slora_last_hip_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        text = lib().slora_strerror(rc).decode()
+        if rc == SLORA_EHIP:
+            text += " (" + lib().slora_last_hip_error().decode() + ")"
+        raise SloraError(rc, text)
+
+
+def _p(t):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream
+
+
+def _ptr_array(items):
+    return (ctypes.c_void_p * len(items))(*[_p(t) for t in items])
+
+
+# ---- same names as the C ABI -----------------------------------------------------------------
+def slora_create(d_model, n_head, d_ff, n_blocks, lora_r, lora_alpha, lora_mask, max_seqs, seq_len,
+                 dtype=DTYPE_BF16, ln_eps=1e-5):
+    cfg = slora_config(d_model, n_head, d_ff, n_blocks, lora_r, lora_alpha, lora_mask, dtype, ln_eps,
+                       max_seqs, seq_len)
+    h = ctypes.c_void_p()
+    _check(lib().slora_create(ctypes.byref(cfg), ctypes.byref(h)))
+    return h
+
+
+def slora_destroy(ctx):
+    _check(lib().slora_destroy(ctx))
+
+
+def slora_workspace_bytes(ctx):
+    return int(lib().slora_workspace_bytes(ctx))
+
+
+def slora_bind_workspace(ctx, ws, nbytes):
+    _check(lib().slora_bind_workspace(ctx, _p(ws), nbytes))
+
+
+def slora_bind_frozen(ctx, block, which, w):
+    _check(lib().slora_bind_frozen(ctx, block, which, _p(w)))
+
+
+def slora_bind_adapter(ctx, block, proj, A, B, dA, dB):
+    _check(lib().slora_bind_adapter(ctx, block, proj, _p(A), _p(B), _p(dA), _p(dB)))
+
+
+def slora_server_fwd(ctx, x_clients, batch, y, stream=None):
+    K = len(x_clients)
+    b = (ctypes.c_int32 * K)(*[int(v) for v in batch])
+    _check(lib().slora_server_fwd(ctx, K, _ptr_array(x_clients), b, _p(y), _stream(stream)))
+
+
+def slora_server_bwd(ctx, dy, dx_clients, stream=None):
+    _check(lib().slora_server_bwd(ctx, _p(dy), _ptr_array(dx_clients), _stream(stream)))
+
+
+def slora_adapter_step(ctx, lr, stream=None):
+    _check(lib().slora_adapter_step(ctx, lr, _stream(stream)))
+
+
+def slora_fedavg(client_params, sample_counts, n, out, stream=None):
+    K = len(client_params)
+    cnt = (ctypes.c_int64 * K)(*[int(v) for v in sample_counts])
+    _check(lib().slora_fedavg(K, _ptr_array(client_params), cnt, n, _p(out), _stream(stream)))
+
+
+def slora_lora_linear_ws_bytes(dtype, T, n_in, n_out, r):
+    return int(lib().slora_lora_linear_ws_bytes(dtype, T, n_in, n_out, r))
+
+
+def slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, x, W, bias, A, B, y, ws, ws_bytes, stream=None):
+    _check(lib().slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, _p(x), _p(W), _p(bias), _p(A), _p(B),
+                                       _p(y), _p(ws), ws_bytes, _stream(stream)))
+
+
+def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, dA, dB, ws, ws_bytes, stream=None):
+    _check(lib().slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, _p(x), _p(dy), _p(W), _p(A), _p(B),
+                                       _p(dx), _p(dA), _p(dB), _p(ws), ws_bytes, _stream(stream)))
+
+
+# ---- buffer management for tests and the benchmark (allocation + marshalling only) -----------------
+def to_device_bf16(a):
+    """float32 numpy array of bf16-representable values -> torch bf16 tensor on the GPU."""
+    import torch
+    from . import synth
+    bits = synth.bf16_bits(a).reshape(np.shape(a))
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def from_device_bf16(t):
+    """torch bf16 tensor -> float32 numpy array."""
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+class Server:
+    """Owns the device buffers of one server stack and forwards to the C ABI.
+
+    blocks / adapters: as produced by synth.make_stack_inputs (numpy float32)."""
+
+    def __init__(self, cfg, blocks, adapters, max_seqs=None):
+        import torch
+        self.cfg = cfg
+        mask = 0
+        for p in cfg.lora_proj:
+            mask |= 1 << PROJ[p]
+        self.max_seqs = max_seqs or cfg.n_seq
+        self.ctx = slora_create(cfg.d_model, cfg.n_head, cfg.d_ff, len(blocks), cfg.lora_r, cfg.lora_alpha, mask,
+                                self.max_seqs, cfg.seq_len, DTYPE_BF16, cfg.ln_eps)
+        self.ws_bytes = slora_workspace_bytes(self.ctx)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device="cuda")
+        base = self.ws.data_ptr()
+        self._ws_ptr = (base + 255) & ~255
+        slora_bind_workspace(self.ctx, self._ws_ptr, self.ws_bytes)
+        self.frozen = []
+        for l, blk in enumerate(blocks):
+            dev = {k: to_device_bf16(v) for k, v in blk.items()}
+            self.frozen.append(dev)
+            for k, t in dev.items():
+                slora_bind_frozen(self.ctx, l, FROZEN[k], t)
+        self.adapters = []
+        for l, ad in enumerate(adapters):
+            dev = {}
+            for p, (A, B) in ad.items():
+                tA = torch.from_numpy(np.ascontiguousarray(A, dtype=np.float32)).cuda()
+                tB = torch.from_numpy(np.ascontiguousarray(B, dtype=np.float32)).cuda()
+                dA, dB = torch.zeros_like(tA), torch.zeros_like(tB)
+                dev[p] = (tA, tB, dA, dB)
+                slora_bind_adapter(self.ctx, l, PROJ[p], tA, tB, dA, dB)
+            self.adapters.append(dev)
+
+    def fwd(self, x_clients, y, stream=None):
+        slora_server_fwd(self.ctx, x_clients, [t.shape[0] for t in x_clients], y, stream)
+
+    def bwd(self, dy, dx_clients, stream=None):
+        slora_server_bwd(self.ctx, dy, dx_clients, stream)
+
+    def step(self, lr, stream=None):
+        slora_adapter_step(self.ctx, lr, stream)
+
+    def close(self):
+        if self.ctx is not None:
+            slora_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,732 @@
+// C ABI of libslora: context, workspace layout and the per-block kernel schedule of the
+// server-side step of split federated LoRA fine-tuning (SplitLoRA Sec. III-B a3, a4, b2).
+// Host code only; every device operation is a kernel launch (or one async table upload)
+// on the caller's stream.
+#include "../../include/slora.h"
+#include "common.h"
+
+#include <array>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+int f32_lora_linear_fwd(int T, int n_in, int n_out, int r, float s, const float *x, const float *W,
+                        const float *bias, const float *A, const float *B, float *y, float *ws, hipStream_t st);
+int f32_lora_linear_bwd(int T, int n_in, int n_out, int r, float s, const float *x, const float *dy,
+                        const float *W, const float *A, const float *B, float *dx, float *dA, float *dB, float *ws,
+                        hipStream_t st);
+
+// ---- descriptor-driven batched kernels (one launch for every adapter of every block) ----------
+struct CastDesc {            // fp32 [rows,cols] (optionally transposed) -> bf16 block [drows,dcols], pitch ld
+    const float *src; bf16 *dst;
+    int rows, cols, transpose, ld, drows, dcols;
+};
+struct SgdDesc { float *p; const float *g; int n; int pad; };
+
+__global__ __launch_bounds__(256) void cast_table_kernel(const CastDesc *__restrict__ tab)
+{
+    const CastDesc d = tab[blockIdx.y];
+    const int total = d.drows * d.dcols;
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
+        const int i = idx / d.dcols, j = idx - i * d.dcols;
+        float v = 0.f;
+        if (!d.transpose) {
+            if (i < d.rows && j < d.cols) v = d.src[(size_t)i * d.cols + j];
+        } else {
+            if (j < d.rows && i < d.cols) v = d.src[(size_t)j * d.cols + i];
+        }
+        d.dst[(size_t)i * d.ld + j] = f2bf(v);
+    }
+}
+
+__global__ __launch_bounds__(256) void sgd_table_kernel(const SgdDesc *__restrict__ tab, float lr)
+{
+    const SgdDesc d = tab[blockIdx.y];
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < d.n; i += gridDim.x * 256)
+        d.p[i] = __fmaf_rn(-lr, d.g[i], d.p[i]);
+}
+
+// ---- error text --------------------------------------------------------------------------------
+static thread_local char g_hip_err[256] = "";
+const char *set_hip_error(hipError_t e, const char *where)
+{
+    snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", where, hipGetErrorString(e));
+    return g_hip_err;
+}
+
+namespace {
+
+inline size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct AdapterBind { float *A, *B, *dA, *dB; };
+
+struct BlockWs {
+    // persistent: transposed frozen weights and bf16 adapter shadows
+    size_t WqkvT, WoT, WfcT, WprT;
+    size_t fz[SLORA_NPROJ], ft[SLORA_NPROJ];   // forward: down-projection [32,in], up-projection [out,16]
+    size_t bz[SLORA_NPROJ], bt[SLORA_NPROJ];   // backward (o, fc, pr): B^T [32,out], A^T [in,16]
+    size_t bz_qkv, bt_qkv;                     // backward, fused q|k|v: block-diagonal B^T [NZ,3d], A^T [d,K2]
+    // saved between forward and backward
+    size_t h_in, stats1, qkv, o, lse, h_mid, stats2, f, u, u2, g;
+    size_t zs[SLORA_NPROJ];
+};
+
+}  // namespace
+
+struct slora_ctx {
+    slora_config cfg;
+    int d, H, dff, L, r, S, maxT;
+    float s;
+    uint32_t mask;
+    int n_qkv, qkv_idx[3], nz_qkv, k2_qkv;     // adapters among q,k,v and their slot in the fused operands
+    std::vector<std::array<const bf16 *, SLORA_NFROZEN>> frozen;
+    std::vector<std::array<AdapterBind, SLORA_NPROJ>> adapters;
+    std::vector<BlockWs> bw;
+    // transients
+    size_t t_u, t_u2, t_g, t_df, t_du2, t_do, t_dqkv, t_du, t_ps, t_delta, t_part;
+    size_t t_dh32[2], t_dh16[2];
+    size_t shadow_begin, shadow_end, cast_tab, sgd_tab;
+    std::vector<CastDesc> h_cast;
+    std::vector<SgdDesc> h_sgd;
+    size_t need;
+    char *ws;
+    size_t ws_bytes;
+    bool prepared, shadows_dirty;
+    int state;                                  // 0 idle, 1 forward done, 2 backward done
+    int K, n_seq, T;
+    int row_end[SLORA_MAX_CLIENTS];
+};
+
+namespace {
+
+void proj_shape(const slora_ctx *c, int p, int &n_in, int &n_out)
+{
+    n_in = (p == SLORA_PROJ_PR) ? c->dff : c->d;
+    n_out = (p == SLORA_PROJ_FC) ? c->dff : c->d;
+}
+inline bool adapted(const slora_ctx *c, int p) { return (c->mask >> p) & 1u; }
+
+void plan_workspace(slora_ctx *c)
+{
+    const size_t T = (size_t)c->maxT, d = c->d, dff = c->dff, H = c->H;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = al256(off + bytes); return o; };
+    c->bw.resize(c->L);
+    for (int l = 0; l < c->L; ++l) {
+        BlockWs &b = c->bw[l];
+        b.WqkvT = take(2 * d * 3 * d);
+        b.WoT = take(2 * d * d);
+        b.WfcT = take(2 * d * dff);
+        b.WprT = take(2 * dff * d);
+    }
+    c->shadow_begin = off;
+    for (int l = 0; l < c->L; ++l) {
+        BlockWs &b = c->bw[l];
+        for (int p = 0; p < SLORA_NPROJ; ++p) {
+            b.fz[p] = b.ft[p] = b.bz[p] = b.bt[p] = 0;
+            if (!adapted(c, p)) continue;
+            int n_in, n_out;
+            proj_shape(c, p, n_in, n_out);
+            b.fz[p] = take(2 * 32 * (size_t)n_in);
+            b.ft[p] = take(2 * (size_t)n_out * SL_RP);
+            if (p >= SLORA_PROJ_O) {
+                b.bz[p] = take(2 * 32 * (size_t)n_out);
+                b.bt[p] = take(2 * (size_t)n_in * SL_RP);
+            }
+        }
+        b.bz_qkv = b.bt_qkv = 0;
+        if (c->n_qkv) {
+            b.bz_qkv = take(2 * (size_t)c->nz_qkv * 3 * d);
+            b.bt_qkv = take(2 * d * (size_t)c->k2_qkv);
+        }
+    }
+    c->shadow_end = off;
+    c->cast_tab = take(sizeof(CastDesc) * (size_t)c->L * SLORA_NPROJ * 4);
+    c->sgd_tab = take(sizeof(SgdDesc) * (size_t)c->L * SLORA_NPROJ * 2);
+    const bool qkv_ad = c->n_qkv > 0;
+    for (int l = 0; l < c->L; ++l) {
+        BlockWs &b = c->bw[l];
+        b.h_in = take(4 * T * d);
+        b.stats1 = take(8 * T);
+        b.qkv = take(2 * T * 3 * d);
+        b.o = take(2 * T * d);
+        b.lse = take(4 * T * H);
+        b.h_mid = take(4 * T * d);
+        b.stats2 = take(8 * T);
+        b.f = take(2 * T * dff);
+        b.u = qkv_ad ? take(2 * T * d) : 0;
+        b.u2 = adapted(c, SLORA_PROJ_FC) ? take(2 * T * d) : 0;
+        b.g = adapted(c, SLORA_PROJ_PR) ? take(2 * T * dff) : 0;
+        for (int p = 0; p < SLORA_NPROJ; ++p) b.zs[p] = adapted(c, p) ? take(2 * T * SL_RP) : 0;
+    }
+    c->t_u = take(2 * T * d);
+    c->t_u2 = take(2 * T * d);
+    c->t_g = take(2 * T * dff);
+    c->t_df = take(2 * T * dff);
+    c->t_du2 = take(2 * T * d);
+    c->t_do = take(2 * T * d);
+    c->t_dqkv = take(2 * T * 3 * d);
+    c->t_du = take(2 * T * d);
+    c->t_ps = take(2 * T * 64);
+    c->t_delta = take(4 * T * H);
+    c->t_part = take(4 * lora_grad_partial_floats(c->maxT, (int)(dff > d ? dff : d)));
+    for (int i = 0; i < 2; ++i) {
+        c->t_dh32[i] = take(4 * T * d);
+        c->t_dh16[i] = take(2 * T * d);
+    }
+    c->need = off;
+}
+
+template <class Tp>
+inline Tp *at(const slora_ctx *c, size_t off) { return (Tp *)(c->ws + off); }
+
+void build_tables(slora_ctx *c)
+{
+    c->h_cast.clear();
+    c->h_sgd.clear();
+    for (int l = 0; l < c->L; ++l) {
+        const BlockWs &b = c->bw[l];
+        for (int p = 0; p < SLORA_NPROJ; ++p) {
+            if (!adapted(c, p)) continue;
+            const AdapterBind &ab = c->adapters[l][p];
+            int n_in, n_out;
+            proj_shape(c, p, n_in, n_out);
+            // forward operands
+            c->h_cast.push_back({ab.A, at<bf16>(c, b.fz[p]), c->r, n_in, 0, n_in, 32, n_in});
+            c->h_cast.push_back({ab.B, at<bf16>(c, b.ft[p]), n_out, c->r, 0, SL_RP, n_out, SL_RP});
+            // backward operands
+            if (p >= SLORA_PROJ_O) {
+                c->h_cast.push_back({ab.B, at<bf16>(c, b.bz[p]), n_out, c->r, 1, n_out, 32, n_out});
+                c->h_cast.push_back({ab.A, at<bf16>(c, b.bt[p]), c->r, n_in, 1, SL_RP, n_in, SL_RP});
+            } else {
+                const int idx = c->qkv_idx[p];
+                // rows 16 idx .. of the block-diagonal B^T, columns p d ..; other entries stay zero
+                c->h_cast.push_back({ab.B, at<bf16>(c, b.bz_qkv) + (size_t)16 * idx * 3 * c->d + (size_t)p * c->d,
+                                     n_out, c->r, 1, 3 * c->d, SL_RP, n_out});
+                c->h_cast.push_back({ab.A, at<bf16>(c, b.bt_qkv) + 16 * idx, c->r, n_in, 1, c->k2_qkv, n_in, SL_RP});
+            }
+            c->h_sgd.push_back({ab.A, ab.dA, c->r * n_in, 0});
+            c->h_sgd.push_back({ab.B, ab.dB, n_out * c->r, 0});
+        }
+    }
+}
+
+int refresh_shadows(slora_ctx *c, hipStream_t st)
+{
+    if (c->h_cast.empty()) return 0;
+    const int max_elems = 32 * (c->dff > c->d ? c->dff : c->d);
+    int gx = (max_elems + 255) / 256;
+    if (gx > 64) gx = 64;
+    hipLaunchKernelGGL(cast_table_kernel, dim3(gx, (unsigned)c->h_cast.size()), dim3(256), 0, st,
+                       at<CastDesc>(c, c->cast_tab));
+    SL_CHECK_LAUNCH("cast_table");
+    return 0;
+}
+
+int prepare(slora_ctx *c, hipStream_t st)
+{
+    int rc;
+    build_tables(c);
+    if (!c->h_cast.empty()) {
+        hipError_t e = hipMemcpyAsync(at<void>(c, c->cast_tab), c->h_cast.data(), sizeof(CastDesc) * c->h_cast.size(),
+                                      hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) { set_hip_error(e, "upload cast table"); return SLORA_EHIP; }
+        e = hipMemcpyAsync(at<void>(c, c->sgd_tab), c->h_sgd.data(), sizeof(SgdDesc) * c->h_sgd.size(),
+                           hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) { set_hip_error(e, "upload sgd table"); return SLORA_EHIP; }
+        if ((rc = launch_fill_zero(at<void>(c, c->shadow_begin), c->shadow_end - c->shadow_begin, st))) return rc;
+    }
+    for (int l = 0; l < c->L; ++l) {
+        const BlockWs &b = c->bw[l];
+        const auto &fz = c->frozen[l];
+        if ((rc = launch_transpose_bf16(fz[SLORA_WQKV], 3 * c->d, c->d, at<bf16>(c, b.WqkvT), st))) return rc;
+        if ((rc = launch_transpose_bf16(fz[SLORA_WO], c->d, c->d, at<bf16>(c, b.WoT), st))) return rc;
+        if ((rc = launch_transpose_bf16(fz[SLORA_WFC], c->dff, c->d, at<bf16>(c, b.WfcT), st))) return rc;
+        if ((rc = launch_transpose_bf16(fz[SLORA_WPR], c->d, c->dff, at<bf16>(c, b.WprT), st))) return rc;
+    }
+    c->prepared = true;
+    c->shadows_dirty = true;
+    return 0;
+}
+
+int check_bound(const slora_ctx *c)
+{
+    if (!c->ws) return SLORA_ESTATE;
+    for (int l = 0; l < c->L; ++l) {
+        for (int w = 0; w < SLORA_NFROZEN; ++w)
+            if (!c->frozen[l][w]) return SLORA_ESTATE;
+        for (int p = 0; p < SLORA_NPROJ; ++p)
+            if (adapted(c, p)) {
+                const AdapterBind &ab = c->adapters[l][p];
+                if (!ab.A || !ab.B || !ab.dA || !ab.dB) return SLORA_ESTATE;
+            }
+    }
+    return 0;
+}
+
+// one frozen linear with optional adapter: fills the common GemmArgs fields
+GemmArgs gemm_base(const bf16 *X, int ldx, const bf16 *W, int M, int N, int K, const bf16 *bias, float s)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.X = X; a.ldx = ldx; a.W = W; a.ldw = K; a.M = M; a.N = N; a.K = K;
+    a.nseg = 1; a.seg_n = N; a.bias = bias; a.ldo = N; a.zscale = s; a.K2 = 16; a.ldz = K; a.ldt = 16;
+    return a;
+}
+
+int lora_grads(slora_ctx *c, int l, int p, const bf16 *x, int ldx, const bf16 *dy, int ldy_, const bf16 *ps, int ldps,
+               hipStream_t st)
+{
+    int n_in, n_out, rc;
+    proj_shape(c, p, n_in, n_out);
+    const AdapterBind &ab = c->adapters[l][p];
+    float *part = at<float>(c, c->t_part);
+    // dA [r,in] = ps^T x
+    if ((rc = launch_lora_grad(x, ldx, n_in, ps, ldps, c->r, c->T, part, ab.dA, 1, st))) return rc;
+    // dB [out,r] = dy^T zs
+    return launch_lora_grad(dy, ldy_, n_out, at<bf16>(c, c->bw[l].zs[p]), SL_RP, c->r, c->T, part, ab.dB, 0, st);
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+const char *slora_strerror(int code)
+{
+    switch (code) {
+    case SLORA_OK: return "ok";
+    case SLORA_EINVAL: return "invalid argument or unsupported configuration";
+    case SLORA_ESTATE: return "call order violated or weights/adapters/workspace not bound";
+    case SLORA_ENOSPC: return "workspace too small";
+    case SLORA_EHIP: return "HIP call failed";
+    case SLORA_EZERO: return "negative sample count or zero total";
+    }
+    return "unknown error";
+}
+
+const char *slora_last_hip_error(void) { return g_hip_err; }
+
+int slora_create(const slora_config *cfg, slora_ctx **out)
+{
+    if (!cfg || !out) return SLORA_EINVAL;
+    *out = nullptr;
+    if (cfg->dtype != SLORA_DTYPE_BF16) return SLORA_EINVAL;
+    if (cfg->d_model <= 0 || cfg->n_head <= 0 || cfg->d_model % 64 || cfg->d_model != cfg->n_head * 64)
+        return SLORA_EINVAL;
+    if (cfg->d_model > 2048) return SLORA_EINVAL;
+    if (cfg->d_ff <= 0 || cfg->d_ff % 64) return SLORA_EINVAL;
+    if (cfg->n_blocks <= 0 || cfg->n_blocks > 1024) return SLORA_EINVAL;
+    if (cfg->lora_r < 1 || cfg->lora_r > SLORA_MAX_RANK) return SLORA_EINVAL;
+    if (cfg->lora_mask >> SLORA_NPROJ) return SLORA_EINVAL;
+    if (!(cfg->ln_eps > 0.f) || !(cfg->lora_alpha == cfg->lora_alpha)) return SLORA_EINVAL;
+    if (cfg->max_seqs <= 0 || cfg->seq_len <= 0 || cfg->seq_len % 64) return SLORA_EINVAL;
+    if ((long long)cfg->max_seqs * cfg->seq_len > (1ll << 24)) return SLORA_EINVAL;
+    slora_ctx *c = new (std::nothrow) slora_ctx();
+    if (!c) return SLORA_EINVAL;
+    c->cfg = *cfg;
+    c->d = cfg->d_model; c->H = cfg->n_head; c->dff = cfg->d_ff; c->L = cfg->n_blocks; c->r = cfg->lora_r;
+    c->S = cfg->seq_len; c->maxT = cfg->max_seqs * cfg->seq_len;
+    c->s = cfg->lora_alpha / (float)cfg->lora_r;
+    c->mask = cfg->lora_mask;
+    c->n_qkv = 0;
+    for (int p = 0; p < 3; ++p) c->qkv_idx[p] = adapted(c, p) ? c->n_qkv++ : -1;
+    c->nz_qkv = c->n_qkv <= 2 ? 32 : 64;
+    c->k2_qkv = 16 * c->n_qkv;
+    c->frozen.assign(c->L, {});
+    c->adapters.assign(c->L, {});
+    c->ws = nullptr; c->ws_bytes = 0;
+    c->prepared = false; c->shadows_dirty = true; c->state = 0;
+    c->K = 0; c->n_seq = 0; c->T = 0;
+    plan_workspace(c);
+    *out = c;
+    return SLORA_OK;
+}
+
+int slora_destroy(slora_ctx *ctx)
+{
+    if (!ctx) return SLORA_EINVAL;
+    delete ctx;
+    return SLORA_OK;
+}
+
+size_t slora_workspace_bytes(const slora_ctx *ctx) { return ctx ? ctx->need : 0; }
+
+int slora_bind_workspace(slora_ctx *ctx, void *ws, size_t bytes)
+{
+    if (!ctx || !ws) return SLORA_EINVAL;
+    if (((uintptr_t)ws) & 255) return SLORA_EINVAL;
+    if (bytes < ctx->need) return SLORA_ENOSPC;
+    ctx->ws = (char *)ws;
+    ctx->ws_bytes = bytes;
+    ctx->prepared = false;
+    ctx->state = 0;
+    return SLORA_OK;
+}
+
+int slora_bind_frozen(slora_ctx *ctx, int block, int which, const void *w)
+{
+    if (!ctx || !w || block < 0 || block >= ctx->L || which < 0 || which >= SLORA_NFROZEN) return SLORA_EINVAL;
+    if (((uintptr_t)w) & 15) return SLORA_EINVAL;
+    ctx->frozen[block][which] = (const bf16 *)w;
+    ctx->prepared = false;
+    ctx->state = 0;
+    return SLORA_OK;
+}
+
+int slora_bind_adapter(slora_ctx *ctx, int block, int proj, float *A, float *B, float *dA, float *dB)
+{
+    if (!ctx || !A || !B || !dA || !dB || block < 0 || block >= ctx->L || proj < 0 || proj >= SLORA_NPROJ)
+        return SLORA_EINVAL;
+    if (!adapted(ctx, proj)) return SLORA_EINVAL;
+    if ((((uintptr_t)A) | ((uintptr_t)B) | ((uintptr_t)dA) | ((uintptr_t)dB)) & 15) return SLORA_EINVAL;
+    ctx->adapters[block][proj] = {A, B, dA, dB};
+    ctx->prepared = false;
+    ctx->state = 0;
+    return SLORA_OK;
+}
+
+int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const int32_t *h_batch, void *y,
+                     void *stream)
+{
+    if (!c || !h_x_clients || !h_batch || !y) return SLORA_EINVAL;
+    if (K <= 0 || K > SLORA_MAX_CLIENTS) return SLORA_EINVAL;
+    long long nseq = 0;
+    for (int i = 0; i < K; ++i) {
+        if (!h_x_clients[i] || h_batch[i] <= 0) return SLORA_EINVAL;
+        if (((uintptr_t)h_x_clients[i]) & 7) return SLORA_EINVAL;
+        nseq += h_batch[i];
+    }
+    if (nseq > c->cfg.max_seqs) return SLORA_EINVAL;
+    if (((uintptr_t)y) & 7) return SLORA_EINVAL;
+    int rc;
+    if ((rc = check_bound(c))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (!c->prepared && (rc = prepare(c, st))) return rc;
+    if (c->shadows_dirty) {
+        if ((rc = refresh_shadows(c, st))) return rc;
+        c->shadows_dirty = false;
+    }
+    c->K = K; c->n_seq = (int)nseq; c->T = c->n_seq * c->S;
+    ClientTable tab;
+    tab.K = K;
+    int rows = 0;
+    for (int i = 0; i < K; ++i) {
+        rows += h_batch[i] * c->S;
+        tab.ptr[i] = (void *)h_x_clients[i];
+        tab.row_end[i] = rows;
+        c->row_end[i] = rows;
+    }
+    c->state = 0;
+    const int T = c->T, d = c->d, dff = c->dff;
+    for (int l = 0; l < c->L; ++l) {
+        const BlockWs &b = c->bw[l];
+        const auto &fz = c->frozen[l];
+        float *h_in = at<float>(c, b.h_in);
+        bf16 *u = at<bf16>(c, b.u ? b.u : c->t_u);
+        // LN1 (block 0 gathers the clients' activations: S = [s_1; ...; s_N])
+        if ((rc = launch_ln_fwd(l == 0 ? nullptr : h_in, l == 0 ? &tab : nullptr, h_in, fz[SLORA_LN1_G],
+                                fz[SLORA_LN1_B], c->cfg.ln_eps, u, at<float>(c, b.stats1), T, d, st)))
+            return rc;
+        // q | k | v = u Wqkv^T + b (+ adapters)
+        {
+            GemmArgs a = gemm_base(u, d, fz[SLORA_WQKV], T, 3 * d, d, fz[SLORA_BQKV], c->s);
+            a.nseg = 3; a.seg_n = d; a.out0 = at<bf16>(c, b.qkv); a.ldo = 3 * d;
+            for (int p = 0; p < 3; ++p)
+                if (adapted(c, p)) {
+                    a.zmat[p] = at<bf16>(c, b.fz[p]); a.tmat[p] = at<bf16>(c, b.ft[p]);
+                    a.zspill[p] = at<bf16>(c, b.zs[p]);
+                }
+            if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? 32 : 0, st))) return rc;
+        }
+        if ((rc = launch_attn_fwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<float>(c, b.lse), c->n_seq, c->S, c->H,
+                                  st)))
+            return rc;
+        // h' = h + o Wo^T + bo (+ adapter)
+        {
+            GemmArgs a = gemm_base(at<bf16>(c, b.o), d, fz[SLORA_WO], T, d, d, fz[SLORA_BO], c->s);
+            a.aux = h_in; a.out0 = at<float>(c, b.h_mid);
+            const bool ad = adapted(c, SLORA_PROJ_O);
+            if (ad) {
+                a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_O]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_O]);
+                a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_O]);
+            }
+            if ((rc = launch_gemm(a, EPI_RESID, ad ? 32 : 0, st))) return rc;
+        }
+        bf16 *u2 = at<bf16>(c, b.u2 ? b.u2 : c->t_u2);
+        if ((rc = launch_ln_fwd(at<float>(c, b.h_mid), nullptr, nullptr, fz[SLORA_LN2_G], fz[SLORA_LN2_B],
+                                c->cfg.ln_eps, u2, at<float>(c, b.stats2), T, d, st)))
+            return rc;
+        // f = u2 Wfc^T + bfc (+ adapter); g = GELU(f)
+        bf16 *g = at<bf16>(c, b.g ? b.g : c->t_g);
+        {
+            GemmArgs a = gemm_base(u2, d, fz[SLORA_WFC], T, dff, d, fz[SLORA_BFC], c->s);
+            a.out0 = at<bf16>(c, b.f); a.out1 = g;
+            const bool ad = adapted(c, SLORA_PROJ_FC);
+            if (ad) {
+                a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_FC]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_FC]);
+                a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_FC]);
+            }
+            if ((rc = launch_gemm(a, EPI_GELU, ad ? 32 : 0, st))) return rc;
+        }
+        // h'' = h' + g Wpr^T + bpr (+ adapter): next block's input, or y for the last block
+        {
+            GemmArgs a = gemm_base(g, dff, fz[SLORA_WPR], T, d, dff, fz[SLORA_BPR], c->s);
+            a.aux = at<float>(c, b.h_mid);
+            if (l + 1 < c->L) a.out0 = at<float>(c, c->bw[l + 1].h_in);
+            else a.out1 = y;
+            const bool ad = adapted(c, SLORA_PROJ_PR);
+            if (ad) {
+                a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_PR]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_PR]);
+                a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_PR]);
+            }
+            if ((rc = launch_gemm(a, EPI_RESID, ad ? 32 : 0, st))) return rc;
+        }
+    }
+    c->state = 1;
+    return SLORA_OK;
+}
+
+int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, void *stream)
+{
+    if (!c || !dy || !h_dx_clients) return SLORA_EINVAL;
+    if (c->state != 1) return SLORA_ESTATE;
+    for (int i = 0; i < c->K; ++i)
+        if (!h_dx_clients[i] || (((uintptr_t)h_dx_clients[i]) & 7)) return SLORA_EINVAL;
+    if (((uintptr_t)dy) & 15) return SLORA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    ClientTable tab;
+    tab.K = c->K;
+    for (int i = 0; i < c->K; ++i) { tab.ptr[i] = h_dx_clients[i]; tab.row_end[i] = c->row_end[i]; }
+    const int T = c->T, d = c->d, dff = c->dff;
+    int rc;
+    // gradient of the residual stream entering the block from above: fp32 (+ bf16 GEMM operand)
+    const float *dh2_32 = nullptr;
+    const bf16 *dh2_16 = (const bf16 *)dy;
+    for (int l = c->L - 1; l >= 0; --l) {
+        const BlockWs &b = c->bw[l];
+        const auto &fz = c->frozen[l];
+        bf16 *df = at<bf16>(c, c->t_df), *ps = at<bf16>(c, c->t_ps);
+        // dg = dh'' Wpr (+ adapter);  df = dg * GELU'(f)
+        {
+            GemmArgs a = gemm_base(dh2_16, d, at<bf16>(c, b.WprT), T, dff, d, nullptr, c->s);
+            a.aux = at<bf16>(c, b.f); a.out0 = df;
+            const bool ad = adapted(c, SLORA_PROJ_PR);
+            if (ad) {
+                a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_PR]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_PR]);
+                a.zspill[0] = ps;
+            }
+            if ((rc = launch_gemm(a, EPI_DGELU, ad ? 32 : 0, st))) return rc;
+            if (ad && (rc = lora_grads(c, l, SLORA_PROJ_PR, at<bf16>(c, b.g), dff, dh2_16, d, ps, SL_RP, st)))
+                return rc;
+        }
+        // du2 = df Wfc (+ adapter)
+        bf16 *du2 = at<bf16>(c, c->t_du2);
+        {
+            GemmArgs a = gemm_base(df, dff, at<bf16>(c, b.WfcT), T, d, dff, nullptr, c->s);
+            a.out0 = du2;
+            const bool ad = adapted(c, SLORA_PROJ_FC);
+            if (ad) {
+                a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_FC]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_FC]);
+                a.zspill[0] = ps;
+            }
+            if ((rc = launch_gemm(a, EPI_STORE, ad ? 32 : 0, st))) return rc;
+            if (ad && (rc = lora_grads(c, l, SLORA_PROJ_FC, at<bf16>(c, b.u2), d, df, dff, ps, SL_RP, st))) return rc;
+        }
+        // dh' = dh'' + LN2^T(du2)
+        float *dh1_32 = at<float>(c, c->t_dh32[1]);
+        bf16 *dh1_16 = at<bf16>(c, c->t_dh16[1]);
+        if ((rc = launch_ln_bwd(du2, at<float>(c, b.h_mid), at<float>(c, b.stats2), fz[SLORA_LN2_G], dh2_32,
+                                dh2_32 ? nullptr : dh2_16, dh1_32, dh1_16, nullptr, T, d, st)))
+            return rc;
+        // do = dh' Wo (+ adapter)
+        bf16 *dob = at<bf16>(c, c->t_do);
+        {
+            GemmArgs a = gemm_base(dh1_16, d, at<bf16>(c, b.WoT), T, d, d, nullptr, c->s);
+            a.out0 = dob;
+            const bool ad = adapted(c, SLORA_PROJ_O);
+            if (ad) {
+                a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_O]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_O]);
+                a.zspill[0] = ps;
+            }
+            if ((rc = launch_gemm(a, EPI_STORE, ad ? 32 : 0, st))) return rc;
+            if (ad && (rc = lora_grads(c, l, SLORA_PROJ_O, at<bf16>(c, b.o), d, dh1_16, d, ps, SL_RP, st))) return rc;
+        }
+        // attention backward
+        bf16 *dqkv = at<bf16>(c, c->t_dqkv);
+        if ((rc = launch_attn_bwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), dob, at<float>(c, b.lse),
+                                  at<float>(c, c->t_delta), dqkv, c->n_seq, c->S, c->H, st)))
+            return rc;
+        // du = [dq dk dv] Wqkv (+ adapters): one GEMM with contraction 3d
+        bf16 *dub = at<bf16>(c, c->t_du);
+        {
+            GemmArgs a = gemm_base(dqkv, 3 * d, at<bf16>(c, b.WqkvT), T, d, 3 * d, nullptr, c->s);
+            a.out0 = dub;
+            if (c->n_qkv) {
+                a.zmat[0] = at<bf16>(c, b.bz_qkv); a.tmat[0] = at<bf16>(c, b.bt_qkv); a.zspill[0] = ps;
+                a.K2 = c->k2_qkv; a.ldt = c->k2_qkv;
+            }
+            if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? c->nz_qkv : 0, st))) return rc;
+            for (int p = 0; p < 3; ++p)
+                if (adapted(c, p) &&
+                    (rc = lora_grads(c, l, p, at<bf16>(c, b.u), d, dqkv + (size_t)p * d, 3 * d,
+                                     ps + 16 * c->qkv_idx[p], c->k2_qkv, st)))
+                    return rc;
+        }
+        // dh = dh' + LN1^T(du): next block's incoming gradient, or the clients' activation gradients
+        float *nx32 = at<float>(c, c->t_dh32[0]);
+        bf16 *nx16 = at<bf16>(c, c->t_dh16[0]);
+        if (l > 0) {
+            if ((rc = launch_ln_bwd(dub, at<float>(c, b.h_in), at<float>(c, b.stats1), fz[SLORA_LN1_G], dh1_32,
+                                    nullptr, nx32, nx16, nullptr, T, d, st)))
+                return rc;
+            dh2_32 = nx32;
+            dh2_16 = nx16;
+        } else {
+            if ((rc = launch_ln_bwd(dub, at<float>(c, b.h_in), at<float>(c, b.stats1), fz[SLORA_LN1_G], dh1_32,
+                                    nullptr, nullptr, nullptr, &tab, T, d, st)))
+                return rc;
+        }
+    }
+    c->state = 2;
+    return SLORA_OK;
+}
+
+int slora_adapter_step(slora_ctx *c, float lr, void *stream)
+{
+    if (!c) return SLORA_EINVAL;
+    if (c->state != 2) return SLORA_ESTATE;
+    if (!(lr == lr)) return SLORA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (!c->h_sgd.empty()) {
+        int max_n = 0;
+        for (const SgdDesc &d : c->h_sgd) max_n = d.n > max_n ? d.n : max_n;
+        int gx = (max_n + 255) / 256;
+        if (gx > 64) gx = 64;
+        hipLaunchKernelGGL(sgd_table_kernel, dim3(gx, (unsigned)c->h_sgd.size()), dim3(256), 0, st,
+                           at<SgdDesc>(c, c->sgd_tab), lr);
+        SL_CHECK_LAUNCH("sgd_table");
+        int rc = refresh_shadows(c, st);
+        if (rc) return rc;
+    }
+    c->shadows_dirty = false;
+    c->state = 0;
+    return SLORA_OK;
+}
+
+int slora_fedavg(int K, const float *const *h_client_params, const int64_t *h_sample_counts, size_t n, float *out,
+                 void *stream)
+{
+    if (!h_client_params || !h_sample_counts || !out) return SLORA_EINVAL;
+    if (K <= 0 || K > SLORA_MAX_CLIENTS) return SLORA_EINVAL;
+    double tot = 0.0;
+    for (int i = 0; i < K; ++i) {
+        if (!h_client_params[i]) return SLORA_EINVAL;
+        if (h_sample_counts[i] < 0) return SLORA_EZERO;
+        tot += (double)h_sample_counts[i];
+    }
+    if (!(tot > 0.0)) return SLORA_EZERO;
+    if (n == 0) return SLORA_OK;
+    float w[SLORA_MAX_CLIENTS];
+    for (int i = 0; i < K; ++i) w[i] = (float)((double)h_sample_counts[i] / tot);
+    return launch_fedavg(K, h_client_params, w, n, out, (hipStream_t)stream);
+}
+
+// ---- single layer -----------------------------------------------------------------------------
+namespace {
+struct LinWs { size_t A16, B16, B16T, A16T, zs, ps, WT, ytmp, part, total; };
+LinWs lin_ws(int T, int n_in, int n_out)
+{
+    LinWs w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = al256(off + bytes); return o; };
+    w.A16 = take(2 * 32 * (size_t)n_in);
+    w.B16 = take(2 * (size_t)n_out * 16);
+    w.B16T = take(2 * 32 * (size_t)n_out);
+    w.A16T = take(2 * (size_t)n_in * 16);
+    w.zs = take(2 * (size_t)T * 16);
+    w.ps = take(2 * (size_t)T * 16);
+    w.WT = take(2 * (size_t)n_in * n_out);
+    w.ytmp = take(2 * (size_t)T * n_out);
+    w.part = take(4 * lora_grad_partial_floats(T, n_in > n_out ? n_in : n_out));
+    w.total = off;
+    return w;
+}
+bool lin_args_ok(int dtype, int T, int n_in, int n_out, int r)
+{
+    if (dtype != SLORA_DTYPE_F32 && dtype != SLORA_DTYPE_BF16) return false;
+    if (T <= 0 || n_in <= 0 || n_out <= 0 || r < 1 || r > SLORA_MAX_RANK) return false;
+    if ((long long)T * (n_in > n_out ? n_in : n_out) > (1ll << 31) - 1) return false;
+    if (dtype == SLORA_DTYPE_BF16 && ((n_in % 64) || (n_out % 64))) return false;
+    return true;
+}
+}  // namespace
+
+size_t slora_lora_linear_ws_bytes(int dtype, int T, int n_in, int n_out, int r)
+{
+    if (!lin_args_ok(dtype, T, n_in, n_out, r)) return 0;
+    if (dtype == SLORA_DTYPE_F32) return al256(2 * sizeof(float) * (size_t)T * r);
+    return lin_ws(T, n_in, n_out).total;
+}
+
+int slora_lora_linear_fwd(int dtype, int T, int n_in, int n_out, int r, float alpha, const void *x, const void *W,
+                          const void *bias, const float *A, const float *B, void *y, void *ws, size_t ws_bytes,
+                          void *stream)
+{
+    if (!lin_args_ok(dtype, T, n_in, n_out, r) || !x || !W || !A || !B || !y || !ws) return SLORA_EINVAL;
+    if (ws_bytes < slora_lora_linear_ws_bytes(dtype, T, n_in, n_out, r)) return SLORA_ENOSPC;
+    if (((uintptr_t)ws) & 255) return SLORA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const float s = alpha / (float)r;
+    if (dtype == SLORA_DTYPE_F32)
+        return f32_lora_linear_fwd(T, n_in, n_out, r, s, (const float *)x, (const float *)W, (const float *)bias, A,
+                                   B, (float *)y, (float *)ws, st);
+    if ((((uintptr_t)x) | ((uintptr_t)W) | ((uintptr_t)y)) & 15) return SLORA_EINVAL;
+    const LinWs w = lin_ws(T, n_in, n_out);
+    char *base = (char *)ws;
+    int rc;
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 32, n_in, 0, st))) return rc;
+    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16), n_out, 16, 0, st))) return rc;
+    GemmArgs a = gemm_base((const bf16 *)x, n_in, (const bf16 *)W, T, n_out, n_in, (const bf16 *)bias, s);
+    a.zmat[0] = (bf16 *)(base + w.A16); a.tmat[0] = (bf16 *)(base + w.B16); a.zspill[0] = (bf16 *)(base + w.zs);
+    a.out0 = y;
+    return launch_gemm(a, EPI_STORE, 32, st);
+}
+
+int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float alpha, const void *x, const void *dy,
+                          const void *W, const float *A, const float *B, void *dx, float *dA, float *dB, void *ws,
+                          size_t ws_bytes, void *stream)
+{
+    if (!lin_args_ok(dtype, T, n_in, n_out, r) || !x || !dy || !W || !A || !B || !dx || !dA || !dB || !ws)
+        return SLORA_EINVAL;
+    if (ws_bytes < slora_lora_linear_ws_bytes(dtype, T, n_in, n_out, r)) return SLORA_ENOSPC;
+    if (((uintptr_t)ws) & 255) return SLORA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const float s = alpha / (float)r;
+    if (dtype == SLORA_DTYPE_F32)
+        return f32_lora_linear_bwd(T, n_in, n_out, r, s, (const float *)x, (const float *)dy, (const float *)W, A, B,
+                                   (float *)dx, dA, dB, (float *)ws, st);
+    if ((((uintptr_t)x) | ((uintptr_t)W) | ((uintptr_t)dy) | ((uintptr_t)dx)) & 15) return SLORA_EINVAL;
+    const LinWs w = lin_ws(T, n_in, n_out);
+    char *base = (char *)ws;
+    int rc;
+    // the forward's rank-space activations zs = s x A^T are needed by dB: rerun the fused forward
+    if ((rc = slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, x, W, nullptr, A, B, base + w.ytmp, ws, ws_bytes,
+                                    stream)))
+        return rc;
+    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16T), 32, n_out, 1, st))) return rc;
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16T), n_in, 16, 1, st))) return rc;
+    if ((rc = launch_transpose_bf16((const bf16 *)W, n_out, n_in, (bf16 *)(base + w.WT), st))) return rc;
+    GemmArgs a = gemm_base((const bf16 *)dy, n_out, (bf16 *)(base + w.WT), T, n_in, n_out, nullptr, s);
+    a.zmat[0] = (bf16 *)(base + w.B16T); a.tmat[0] = (bf16 *)(base + w.A16T); a.zspill[0] = (bf16 *)(base + w.ps);
+    a.out0 = dx;
+    if ((rc = launch_gemm(a, EPI_STORE, 32, st))) return rc;
+    float *part = (float *)(base + w.part);
+    if ((rc = launch_lora_grad((const bf16 *)x, n_in, n_in, (bf16 *)(base + w.ps), 16, r, T, part, dA, 1, st)))
+        return rc;
+    return launch_lora_grad((const bf16 *)dy, n_out, n_out, (bf16 *)(base + w.zs), 16, r, T, part, dB, 0, st);
+}
+
+}  // extern "C"

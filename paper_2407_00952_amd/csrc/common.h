@@ -1,0 +1,98 @@
+// Internal declarations shared by the HIP sources of libslora (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+typedef __bf16 bf16;
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+#define SL_WAVE 64
+#define SL_RP 16            // adapter rank padded to one MFMA k-step
+#define SL_MAX_CLIENTS 64
+
+static __device__ __forceinline__ float bf2f(bf16 v) { return (float)v; }
+static __device__ __forceinline__ bf16 f2bf(float v) { return (bf16)v; }
+
+// wave-wide sum through DPP-free shuffles (64 lanes)
+static __device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// sigma(2u) with u = sqrt(2/pi) (f + 0.044715 f^3): GELU_tanh(f) = f * sigma(2u)
+static __device__ __forceinline__ float gelu_sig(float f)
+{
+    const float c2 = 1.5957691216057308f;       // 2 sqrt(2/pi)
+    float u2 = c2 * (f + 0.044715f * f * f * f);
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-u2));
+}
+static __device__ __forceinline__ float gelu_fwd(float f) { return f * gelu_sig(f); }
+static __device__ __forceinline__ float gelu_bwd(float f)
+{
+    const float c2 = 1.5957691216057308f;
+    float sg = gelu_sig(f);
+    return sg + f * sg * (1.0f - sg) * c2 * (1.0f + 3.0f * 0.044715f * f * f);
+}
+
+// The K clients' buffers as one logical [sum b_i * S, d] matrix (client-major concatenation).
+struct ClientTable {
+    void *ptr[SL_MAX_CLIENTS];
+    int row_end[SL_MAX_CLIENTS];   // exclusive prefix of rows (tokens)
+    int K;
+};
+
+// ---- GEMM ---------------------------------------------------------------------------------
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_DGELU = 3 };
+
+struct GemmArgs {
+    const bf16 *X; int ldx;          // [M,K]
+    const bf16 *W; int ldw;          // [N,K]  (N = nseg * seg_n)
+    int M, N, K;
+    int nseg, seg_n;
+    const bf16 *bias;                // [N] or null
+    // low-rank branch, per segment (null zmat = segment not adapted)
+    const bf16 *zmat[3]; int ldz;    // [NZ,K]: rows of the down-projection, zero rows beyond the rank
+    const bf16 *tmat[3]; int ldt;    // [seg_n,K2]: up-projection, K2 contiguous
+    bf16 *zspill[3];                 // [M,K2] or null: scaled bf16 copy of the rank-space activations
+    int K2; float zscale;
+    // epilogue
+    void *out0; void *out1; const void *aux; int ldo;
+};
+
+int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);
+
+// ---- elementwise / norm / attention / lora-grad launchers ---------------------------------------
+int launch_ln_fwd(const float *h_f32, const ClientTable *gather /*null unless block 0*/, float *h_copy,
+                  const bf16 *gamma, const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d,
+                  hipStream_t st);
+int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16 *gamma,
+                  const float *dres_f32, const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16,
+                  const ClientTable *scatter, int T, int d, hipStream_t st);
+int launch_attn_fwd(const bf16 *qkv, bf16 *o, float *lse, int n_seq, int S, int H, hipStream_t st);
+int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *dout, const float *lse, float *delta,
+                    bf16 *dqkv, int n_seq, int S, int H, hipStream_t st);
+// G[c, j] = sum_t X[t, c] * Y[t, j], j < r; written transposed ([r, C]) when out_is_rxC.
+int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T,
+                     float *partials, float *out, int out_is_rxC, hipStream_t st);
+size_t lora_grad_partial_floats(int T, int C);
+int launch_fedavg(int K, const float *const *x, const float *w, size_t n, float *out, hipStream_t st);
+int launch_sgd(float *p, const float *g, float lr, size_t n, hipStream_t st);
+int launch_cast_pad(const float *src, int rows, int cols, bf16 *dst, int drows, int dcols, int transpose,
+                    hipStream_t st);
+int launch_transpose_bf16(const bf16 *src, int rows, int cols, bf16 *dst, hipStream_t st);
+int launch_fill_zero(void *p, size_t bytes, hipStream_t st);
+
+const char *set_hip_error(hipError_t e, const char *where);
+#define SL_CHECK_LAUNCH(where)                                          \
+    do {                                                                \
+        hipError_t e__ = hipGetLastError();                             \
+        if (e__ != hipSuccess) { set_hip_error(e__, where); return -4; } \
+    } while (0)

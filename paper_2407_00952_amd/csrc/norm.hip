@@ -1,0 +1,196 @@
+// LayerNorm forward / input-gradient kernels for the frozen GPT-2 blocks of the server stack
+// (SplitLoRA Sec. III-B step a3: the server-side forward and backward; LayerNorm gains and
+// biases are frozen, Sec. III-A, so no parameter gradient is produced).
+//
+// One 64-lane wavefront per token row, the row held in registers, two wave reductions.
+// These kernels are HBM-bound; they also carry the fp32 residual stream:
+//   forward : u = (h - mu) rho * gamma + beta  (bf16 out), stats (mu, rho) saved per row.
+//             For the first server block the input is gathered from the K client buffers
+//             (the concatenation S = [s_1; ...; s_N]) and an fp32 copy of it is kept.
+//   backward: out = dres + rho (g - mean(g) - xhat mean(g xhat)),  g = du * gamma,
+//             written as fp32 (residual gradient) and/or bf16 (next GEMM operand, or the
+//             per-client activation gradient scattered back to the K client buffers).
+#include "common.h"
+
+namespace {
+
+constexpr int MAXC = 8;   // 256-column chunks per row: d <= 2048
+
+__device__ __forceinline__ int client_of(const ClientTable &t, int row, int &local)
+{
+    int c = 0, start = 0;
+    while (c < t.K - 1 && row >= t.row_end[c]) { start = t.row_end[c]; ++c; }
+    local = row - start;
+    return c;
+}
+
+template <bool GATHER>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h, ClientTable tab,
+                                                     float *__restrict__ hcopy, const bf16 *__restrict__ gamma,
+                                                     const bf16 *__restrict__ beta, float eps,
+                                                     bf16 *__restrict__ u, float *__restrict__ stats, int T, int d)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= T) return;
+    float v[MAXC][4];
+    const bf16 *src16 = nullptr;
+    if (GATHER) {
+        int local;
+        int c = client_of(tab, row, local);
+        src16 = (const bf16 *)tab.ptr[c] + (size_t)local * d;
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int col = c * 256 + lane * 4;
+        if (col < d) {
+            if (GATHER) {
+                bf16x4 t = *(const bf16x4 *)(src16 + col);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[c][i] = bf2f(t[i]);
+                *(float4 *)(hcopy + (size_t)row * d + col) = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
+            } else {
+                float4 t = *(const float4 *)(h + (size_t)row * d + col);
+                v[c][0] = t.x; v[c][1] = t.y; v[c][2] = t.z; v[c][3] = t.w;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s += v[c][i];
+        }
+    }
+    const float mu = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        if (c * 256 + lane * 4 < d) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[c][i] -= mu; q += v[c][i] * v[c][i]; }
+        }
+    }
+    const float rho = rsqrtf(wave_sum(q) / (float)d + eps);
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int col = c * 256 + lane * 4;
+        if (col < d) {
+            bf16x4 gm = *(const bf16x4 *)(gamma + col);
+            bf16x4 bt = *(const bf16x4 *)(beta + col);
+            bf16x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = f2bf(v[c][i] * rho * bf2f(gm[i]) + bf2f(bt[i]));
+            *(bf16x4 *)(u + (size_t)row * d + col) = o;
+        }
+    }
+    if (lane == 0) { stats[2 * row] = mu; stats[2 * row + 1] = rho; }
+}
+
+// DRES16: the residual gradient arrives as bf16 (last block: the caller's dY) instead of fp32.
+// SCATTER: the bf16 output goes to the K client buffers.
+template <bool DRES16, bool SCATTER>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du, const float *__restrict__ h,
+                                                     const float *__restrict__ stats, const bf16 *__restrict__ gamma,
+                                                     const void *__restrict__ dres, float *__restrict__ out32,
+                                                     bf16 *__restrict__ out16, ClientTable tab, int T, int d)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= T) return;
+    const float mu = stats[2 * row], rho = stats[2 * row + 1];
+    float gq[MAXC][4], xh[MAXC][4];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int col = c * 256 + lane * 4;
+        if (col < d) {
+            bf16x4 t = *(const bf16x4 *)(du + (size_t)row * d + col);
+            bf16x4 gm = *(const bf16x4 *)(gamma + col);
+            float4 hv = *(const float4 *)(h + (size_t)row * d + col);
+            const float hh[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                gq[c][i] = bf2f(t[i]) * bf2f(gm[i]);
+                xh[c][i] = (hh[i] - mu) * rho;
+                s1 += gq[c][i];
+                s2 += gq[c][i] * xh[c][i];
+            }
+        }
+    }
+    const float m1 = wave_sum(s1) / (float)d;
+    const float m2 = wave_sum(s2) / (float)d;
+    bf16 *dst16 = out16 ? out16 + (size_t)row * d : nullptr;
+    if (SCATTER) {
+        int local;
+        int c = client_of(tab, row, local);
+        dst16 = (bf16 *)tab.ptr[c] + (size_t)local * d;
+    }
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int col = c * 256 + lane * 4;
+        if (col < d) {
+            float r[4];
+            if (DRES16) {
+                bf16x4 t = *(const bf16x4 *)((const bf16 *)dres + (size_t)row * d + col);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) r[i] = bf2f(t[i]);
+            } else {
+                float4 t = *(const float4 *)((const float *)dres + (size_t)row * d + col);
+                r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
+            }
+            bf16x4 o16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                r[i] += rho * (gq[c][i] - m1 - xh[c][i] * m2);
+                o16[i] = f2bf(r[i]);
+            }
+            if (out32) *(float4 *)(out32 + (size_t)row * d + col) = make_float4(r[0], r[1], r[2], r[3]);
+            if (dst16) *(bf16x4 *)(dst16 + col) = o16;
+        }
+    }
+}
+
+}  // namespace
+
+int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, const bf16 *gamma,
+                  const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d, hipStream_t st)
+{
+    if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
+    dim3 grid((T + 3) / 4), block(256);
+    if (gather) {
+        hipLaunchKernelGGL((ln_fwd_kernel<true>), grid, block, 0, st, nullptr, *gather, h_copy, gamma, beta, eps, u,
+                           stats, T, d);
+    } else {
+        ClientTable none;
+        none.K = 0;
+        hipLaunchKernelGGL((ln_fwd_kernel<false>), grid, block, 0, st, h_f32, none, nullptr, gamma, beta, eps, u,
+                           stats, T, d);
+    }
+    SL_CHECK_LAUNCH("ln_fwd");
+    return 0;
+}
+
+int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16 *gamma, const float *dres_f32,
+                  const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16, const ClientTable *scatter, int T, int d,
+                  hipStream_t st)
+{
+    if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
+    dim3 grid((T + 3) / 4), block(256);
+    ClientTable tab;
+    tab.K = 0;
+    if (scatter) tab = *scatter;
+    if (dres_bf16) {
+        if (scatter)
+            hipLaunchKernelGGL((ln_bwd_kernel<true, true>), grid, block, 0, st, du, h, stats, gamma,
+                               (const void *)dres_bf16, out_f32, out_bf16, tab, T, d);
+        else
+            hipLaunchKernelGGL((ln_bwd_kernel<true, false>), grid, block, 0, st, du, h, stats, gamma,
+                               (const void *)dres_bf16, out_f32, out_bf16, tab, T, d);
+    } else {
+        if (scatter)
+            hipLaunchKernelGGL((ln_bwd_kernel<false, true>), grid, block, 0, st, du, h, stats, gamma,
+                               (const void *)dres_f32, out_f32, out_bf16, tab, T, d);
+        else
+            hipLaunchKernelGGL((ln_bwd_kernel<false, false>), grid, block, 0, st, du, h, stats, gamma,
+                               (const void *)dres_f32, out_f32, out_bf16, tab, T, d);
+    }
+    SL_CHECK_LAUNCH("ln_bwd");
+    return 0;
+}

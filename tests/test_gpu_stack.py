@@ -1,0 +1,184 @@
+"""GPU parity of the server-side round (SplitLoRA Sec. III-B a3/a4: forward over the concatenated
+client activations, backward to per-client activation gradients and adapter gradients, SGD step)
+against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import cref
+from paper_2407_00952_amd import binding as B
+from paper_2407_00952_amd import synth
+from gpu_util import BF16_TOL, compare_round, gpu_round, oracle_of, relerr, say
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    "two-blocks-qv": synth.tiny_config(d_model=128, n_head=2, d_ff=256, n_blocks=2, lora_r=4,
+                                       lora_proj=("q", "v"), n_clients=2, batch=1, seq_len=128),
+    "ragged-all-proj": synth.tiny_config(d_model=320, n_head=5, d_ff=704, n_blocks=2, lora_r=3,
+                                         lora_proj=synth.PROJ_NAMES, n_clients=3, batch=1, seq_len=192,
+                                         seed=synth.BASE_SEED + 101),
+    "rank16-qkvo": synth.tiny_config(d_model=256, n_head=4, d_ff=512, n_blocks=1, lora_r=16,
+                                     lora_proj=("q", "k", "v", "o"), n_clients=1, batch=3, seq_len=64,
+                                     seed=synth.BASE_SEED + 102),
+    "no-adapters": synth.tiny_config(d_model=128, n_head=2, d_ff=256, n_blocks=1, lora_r=4, lora_proj=(),
+                                     n_clients=1, batch=2, seq_len=256, seed=synth.BASE_SEED + 103),
+    "rank1-k-fc-pr": synth.tiny_config(d_model=192, n_head=3, d_ff=320, n_blocks=3, lora_r=1,
+                                       lora_proj=("k", "fc", "pr"), n_clients=2, batch=2, seq_len=128,
+                                       seed=synth.BASE_SEED + 104),
+}
+
+
+def _boost_B(inp, factor=8.0):
+    """B ~ N(0, 0.01^2) makes the low-rank term tiny next to x W^T; scale it (bf16-exactly) so that
+    an error in the fused branch cannot hide inside the tolerance."""
+    inp["adapters"] = [{p: (A, synth.round_bf16(Bm * factor)) for p, (A, Bm) in ad.items()}
+                       for ad in inp["adapters"]]
+    return inp
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_stacks(name):
+    cfg = SMALL[name]
+    say("stack", name, cfg)
+    inp = _boost_B(synth.make_stack_inputs(cfg))
+    if name == "ragged-all-proj":                      # unequal batches per client
+        rng = np.random.default_rng(5)
+        inp["clients"] = [synth.round_bf16(rng.standard_normal((b, cfg.seq_len, cfg.d_model)).astype(np.float32))
+                          for b in (1, 2, 1)]
+        inp["dY"] = synth.round_bf16(rng.standard_normal((4, cfg.seq_len, cfg.d_model)).astype(np.float32))
+    srv, Y, dX, grads = gpu_round(cfg, inp)
+    compare_round(cfg, inp, Y, dX, grads, label=name)
+    srv.close()
+
+
+def test_zero_B_equals_base_model_bitwise_on_gpu():
+    cfg = SMALL["ragged-all-proj"]
+    inp = synth.make_stack_inputs(cfg)
+    zeroed = dict(inp)
+    zeroed["adapters"] = [{p: (A, np.zeros_like(Bm)) for p, (A, Bm) in ad.items()} for ad in inp["adapters"]]
+    base_cfg = synth.tiny_config(**{**cfg.__dict__, "lora_proj": ()})
+    base = dict(inp)
+    base["adapters"] = [dict() for _ in inp["adapters"]]
+    s1, Y1, dX1, _ = gpu_round(cfg, zeroed)
+    s0, Y0, dX0, _ = gpu_round(base_cfg, base)
+    assert np.array_equal(Y1, Y0)
+    for a, b in zip(dX1, dX0):
+        assert np.array_equal(a, b)
+    s1.close(); s0.close()
+
+
+def test_backward_is_reproducible_and_clients_are_independent():
+    import torch
+    cfg = SMALL["two-blocks-qv"]
+    inp = _boost_B(synth.make_stack_inputs(cfg))
+    srv, Y, dX, g1 = gpu_round(cfg, inp)
+    _, Y2, dX2, g2 = gpu_round(cfg, inp, server=srv)
+    assert np.array_equal(Y, Y2)
+    for l in range(cfg.n_blocks):
+        for p in cfg.lora_proj:
+            assert g1[l][p][0].tobytes() == g2[l][p][0].tobytes()
+            assert g1[l][p][1].tobytes() == g2[l][p][1].tobytes()
+    # client 1 alone gives the same activation gradient as inside the batch (step a4)
+    _, Ys, dXs, _ = gpu_round(cfg, inp, clients=[inp["clients"][1]], dY=inp["dY"][1:2], server=srv)
+    assert np.array_equal(dXs[0], dX[1]) and np.array_equal(Ys[0], Y[1])
+    srv.close()
+
+
+def test_call_order_and_step():
+    import torch
+    cfg = SMALL["two-blocks-qv"]
+    inp = _boost_B(synth.make_stack_inputs(cfg))
+    srv = B.Server(cfg, inp["blocks"], inp["adapters"])
+    xs = [B.to_device_bf16(c) for c in inp["clients"]]
+    y = torch.empty((cfg.n_seq, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    dy = B.to_device_bf16(inp["dY"])
+    dxs = [torch.empty_like(x) for x in xs]
+    with pytest.raises(B.SloraError) as e:
+        srv.bwd(dy, dxs)
+    assert e.value.code == B.SLORA_ESTATE
+    srv.fwd(xs, y)
+    with pytest.raises(B.SloraError) as e:
+        srv.step(0.01)
+    assert e.value.code == B.SLORA_ESTATE
+    srv.bwd(dy, dxs)
+    torch.cuda.synchronize()
+    before = {(l, p): (t[0].cpu().numpy().copy(), t[1].cpu().numpy().copy(), t[2].cpu().numpy().copy(),
+                       t[3].cpu().numpy().copy()) for l, ad in enumerate(srv.adapters) for p, t in ad.items()}
+    lr = 2e-4
+    srv.step(lr)
+    torch.cuda.synchronize()
+    for (l, p), (A, Bm, dA, dB) in before.items():
+        # Eq. (4),(5), one fused multiply-add per element
+        assert srv.adapters[l][p][0].cpu().numpy().tobytes() == cref.sgd_f32(A, dA, lr).tobytes()
+        assert srv.adapters[l][p][1].cpu().numpy().tobytes() == cref.sgd_f32(Bm, dB, lr).tobytes()
+    with pytest.raises(B.SloraError) as e:
+        srv.step(lr)                                   # needs a new backward
+    assert e.value.code == B.SLORA_ESTATE
+    # the next round uses the updated adapters: compare with the oracle on the stepped values
+    inp2 = dict(inp)
+    inp2["adapters"] = [{p: (t[0].cpu().numpy(), t[1].cpu().numpy()) for p, t in ad.items()} for ad in srv.adapters]
+    _, Y, dX, grads = gpu_round(cfg, inp2, server=srv)
+    compare_round(cfg, inp2, Y, dX, grads, label="after step")
+    srv.close()
+
+
+def test_workload2_full():
+    """GPT-2-small split after block 3: 9 server blocks, r = 4 on q,v, 5 clients x 4 x 512, whole batch."""
+    cfg = synth.CONFIGS[2]
+    say("workload 2:", cfg)
+    inp = synth.make_stack_inputs(cfg)
+    srv, Y, dX, grads = gpu_round(cfg, inp)
+    say("   gpu done; running the fp64 oracle on all %d sequences" % cfg.n_seq)
+    compare_round(cfg, inp, Y, dX, grads, label="workload2")
+    srv.close()
+
+
+def _sampled_parity(cfg, seqs):
+    """Full-size GPU round; the oracle recomputes the sampled sequences one by one (sequences are
+    independent in Y and dx).  Adapter gradients are sums over all tokens, so they are compared on a
+    second GPU round restricted to the sampled sequences."""
+    inp = synth.make_stack_inputs(cfg)
+    say("   inputs ready; full-size GPU round, T = %d tokens" % cfg.tokens)
+    srv, Y, dX, _ = gpu_round(cfg, inp)
+    dX = np.concatenate(dX, axis=0)
+    orc = oracle_of(cfg, inp)
+    allX = np.concatenate(inp["clients"], axis=0)
+    tot = None
+    for n in seqs:
+        y, dx, g = orc.fwd_bwd_sequence(allX[n], inp["dY"][n])
+        ey, ex = relerr(Y[n], y), relerr(dX[n], dx)
+        say("   sequence %d: Y %.2e  dx %.2e" % (n, ey, ex))
+        assert ey <= BF16_TOL and ex <= BF16_TOL
+        if tot is None:
+            tot = g
+        else:
+            tot = [{p: (a[p][0] + b[p][0], a[p][1] + b[p][1]) for p in a} for a, b in zip(tot, g)]
+    sub_clients = [allX[n:n + 1] for n in seqs]
+    sub_dY = np.stack([inp["dY"][n] for n in seqs])
+    _, Ys, _, grads = gpu_round(cfg, inp, clients=sub_clients, dY=sub_dY, server=srv)
+    for i, n in enumerate(seqs):
+        assert np.array_equal(Ys[i], Y[n])
+    worst = 0.0
+    for l in range(cfg.n_blocks):
+        for p in cfg.lora_proj:
+            ea, eb = relerr(grads[l][p][0], tot[l][p][0]), relerr(grads[l][p][1], tot[l][p][1])
+            worst = max(worst, ea, eb)
+            assert ea <= BF16_TOL and eb <= BF16_TOL, (l, p, ea, eb)
+    say("   adapter gradients on the sampled sequences: worst %.2e" % worst)
+    srv.close()
+
+
+def test_workload3_sampled():
+    """GPT-2-medium split after 6: 18 blocks, 8 x 8 x 512 -- the benchmark's launch configuration."""
+    say("workload 3:", synth.CONFIGS[3])
+    _sampled_parity(synth.CONFIGS[3], [0, 37])
+
+
+def test_workload4_sampled():
+    say("workload 4:", synth.CONFIGS[4])
+    _sampled_parity(synth.CONFIGS[4], [13])
+
+
+def test_workload5_sampled():
+    say("workload 5:", synth.CONFIGS[5])
+    _sampled_parity(synth.CONFIGS[5], [50])
