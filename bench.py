@@ -1,0 +1,138 @@
+#!/usr/bin/env python3
+"""Benchmark of the server-side SplitLoRA round on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: server forward over the
+concatenated client activations, backward to the per-client activation gradients and the adapter
+gradients, the SGD adapter step, and the FedAvg of the clients' adapter sets -- all through the C
+ABI of libslora.so.  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak
+
+
+def model_flops_per_token(cfg):
+    """Algorithmic work per token over the whole stack: frozen GEMMs forward + input-gradient (no
+    weight gradient), causal attention forward + backward (lower triangle only), LoRA products."""
+    d, f, S, L, r = cfg.d_model, cfg.d_ff, cfg.seq_len, cfg.n_blocks, cfg.lora_r
+    gemm = 2 * 2 * (4 * d * d + 2 * d * f)
+    attn = 6 * S * d
+    lora = 6 * r * sum(sum(cfg.proj_shape(p)) for p in cfg.lora_proj)
+    return L * gemm, L * attn, L * lora
+
+
+def cpu_baseline(cfg, inp, budget_s=20.0):
+    """The fp64 oracle, as it stands, timed on whole sequences of the same workload."""
+    from oracle import slora_oracle as so
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    orc = so.ServerOracle(inp["blocks"], inp["adapters"], cfg.n_head, cfg.lora_alpha, cfg.lora_r, cfg.ln_eps)
+    x = np.concatenate(inp["clients"][:1], axis=0)
+    n, t0 = 0, time.perf_counter()
+    while True:
+        orc.fwd_bwd_sequence(x[n % x.shape[0]], inp["dY"][n % x.shape[0]])
+        n += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or n >= 4:
+            break
+    return {"value": n * cfg.seq_len / el, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d whole sequence(s) of %d tokens, forward+backward through all %d blocks, numpy fp64"
+                      % (n, cfg.seq_len, cfg.n_blocks)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3, help="2..5 (3 = GPT-2-medium split, the metric's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2407_00952_amd import binding as B
+    from paper_2407_00952_amd import synth
+
+    cfg = synth.CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    inp = synth.make_stack_inputs(cfg)
+    srv = B.Server(cfg, inp["blocks"], inp["adapters"])
+    xs = [B.to_device_bf16(c) for c in inp["clients"]]
+    y = torch.empty((cfg.n_seq, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    dy = B.to_device_bf16(inp["dY"])
+    dxs = [torch.empty_like(x) for x in xs]
+    # FedAvg leg: the K clients' adapter sets (client-side blocks, same rank and projections), fp32
+    n_fed = synth.fedavg_param_count(cfg)
+    fed_vecs, fed_counts = synth.make_fedavg_inputs(cfg.n_clients, n_params=None, cfg=cfg)
+    fed_dev = [torch.from_numpy(v).cuda() for v in fed_vecs]
+    fed_out = torch.empty(n_fed, dtype=torch.float32, device="cuda")
+    lr = 2e-4
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        srv.fwd(xs, y, stream)
+        srv.bwd(dy, dxs, stream)
+        srv.step(lr, stream)
+        B.slora_fedavg(fed_dev, fed_counts, n_fed, fed_out, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.slora_prof_enable(1)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    gemm_ms, gemm_flop, launches = B.slora_prof_read()
+    B.slora_prof_enable(0)
+
+    ms = el / args.steps * 1e3
+    tok_s = cfg.tokens / (el / args.steps)
+    fg, fa, fl = model_flops_per_token(cfg)
+    model_tflops = (fg + fa + fl) * cfg.tokens / (el / args.steps) / 1e12
+    achieved = gemm_flop / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    out = {
+        "metric": "server fwd+bwd tokens/sec on 1 MI355X + % bf16 MFMA peak (GPT-2-medium split)",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d server blocks, d=%d, H=%d, d_ff=%d, LoRA r=%d on %s, K=%d clients x %d x %d "
+                               "tokens (T=%d), bf16 activations; step = fwd + bwd + SGD adapter step + FedAvg of "
+                               "the K client adapter sets" % (cfg.name, cfg.n_blocks, cfg.d_model, cfg.n_head,
+                                                             cfg.d_ff, cfg.lora_r, ",".join(cfg.lora_proj),
+                                                             cfg.n_clients, cfg.batch, cfg.seq_len, cfg.tokens),
+                   "tokens_per_step": cfg.tokens},
+        "model_tflops": model_tflops, "model_frac_of_bf16_peak": model_tflops / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (bf16 MFMA GEMM + fused LoRA branch, all shapes)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
+                     "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
+    }
+    if not args.no_cpu_baseline:
+        del srv
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(cfg, inp)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,15 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
                           const void *x, const void *dy, const void *W, const float *A, const float *B,
                           void *dx, float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- measurement hook (not part of the method) ---------------------------------------------------- */
+/* While enabled, every launch of the bf16 GEMM kernel (the frozen products of Sec. II-C with the
+ * fused low-rank branch) is bracketed by HIP events on its stream.  slora_prof_read waits for the
+ * recorded events (it BLOCKS the host), returns the summed kernel time in milliseconds, the summed
+ * algorithmic work 2*M*N*K in flop and the number of launches recorded (at most 8192 between two
+ * reads), and resets the counters.  Process-wide, not thread-safe. */
+int slora_prof_enable(int on);
+int slora_prof_read(double *h_gemm_ms, double *h_gemm_flop, int *h_launches);
+
 const char *slora_strerror(int code);
 const char *slora_last_hip_error(void);   /* text of the last failed HIP call on this thread */
 

@@ -25,7 +25,8 @@ MAX_RANK, MAX_CLIENTS = 16, 64
 EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind_workspace",
            "slora_bind_frozen", "slora_bind_adapter", "slora_server_fwd", "slora_server_bwd",
            "slora_adapter_step", "slora_fedavg", "slora_lora_linear_ws_bytes", "slora_lora_linear_fwd",
-           "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error"]
+           "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error", "slora_prof_enable",
+           "slora_prof_read"]
 
 
 class slora_config(ctypes.Structure):
@@ -67,6 +68,8 @@ def lib():
         L.slora_lora_linear_ws_bytes.restype = sz
         L.slora_lora_linear_fwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_lora_linear_bwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slora_prof_enable.argtypes = [i32]
+        L.slora_prof_read.argtypes = [vp, vp, vp]
         L.slora_strerror.argtypes = [i32]
         L.slora_strerror.restype = ctypes.c_char_p
         L.slora_last_hip_error.restype = ctypes.c_char_p
@@ -166,6 +169,17 @@ def slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, x, W, bias, A, B, y, 
 def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, dA, dB, ws, ws_bytes, stream=None):
     _check(lib().slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, _p(x), _p(dy), _p(W), _p(A), _p(B),
                                        _p(dx), _p(dA), _p(dB), _p(ws), ws_bytes, _stream(stream)))
+
+
+def slora_prof_enable(on):
+    _check(lib().slora_prof_enable(int(on)))
+
+
+def slora_prof_read():
+    """(gemm_ms, gemm_flop, launches) accumulated since the last read; blocks on the recorded events."""
+    ms, fl, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+    _check(lib().slora_prof_read(ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(n)))
+    return ms.value, fl.value, n.value
 
 
 # ---- buffer management for tests and the benchmark (allocation + marshalling only) -----------------

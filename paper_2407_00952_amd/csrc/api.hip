@@ -17,6 +17,9 @@ int f32_lora_linear_bwd(int T, int n_in, int n_out, int r, float s, const float 
                         const float *W, const float *A, const float *B, float *dx, float *dA, float *dB, float *ws,
                         hipStream_t st);
 
+int gemm_prof_enable(int on);
+int gemm_prof_read(double *ms, double *flop, int *launches);
+
 // ---- descriptor-driven batched kernels (one launch for every adapter of every block) ----------
 struct CastDesc {            // fp32 [rows,cols] (optionally transposed) -> bf16 block [drows,dcols], pitch ld
     const float *src; bf16 *dst;
@@ -307,6 +310,13 @@ const char *slora_strerror(int code)
 }
 
 const char *slora_last_hip_error(void) { return g_hip_err; }
+
+int slora_prof_enable(int on) { return gemm_prof_enable(on) ? SLORA_EHIP : SLORA_OK; }
+
+int slora_prof_read(double *h_gemm_ms, double *h_gemm_flop, int *h_launches)
+{
+    return gemm_prof_read(h_gemm_ms, h_gemm_flop, h_launches) ? SLORA_EHIP : SLORA_OK;
+}
 
 int slora_create(const slora_config *cfg, slora_ctx **out)
 {
