@@ -126,6 +126,12 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
                           const void *x, const void *dy, const void *W, const float *A, const float *B,
                           void *dx, float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
 
+/* The frozen product alone (Sec. II-C with no adapter): y [T,out] = x [T,in] W[out,in]^T + bias, all
+ * bf16 with fp32 accumulation; bias may be NULL; in a multiple of 64.  Runs the same GEMM kernel as the
+ * stack and needs no scratch. */
+int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias,
+                             void *y, void *stream);
+
 /* ---- measurement hook (not part of the method) ---------------------------------------------------- */
 /* While enabled, every launch of the bf16 GEMM kernel (the frozen products of Sec. II-C with the
  * fused low-rank branch) is bracketed by HIP events on its stream.  slora_prof_read waits for the

@@ -26,7 +26,7 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_bind_frozen", "slora_bind_adapter", "slora_server_fwd", "slora_server_bwd",
            "slora_adapter_step", "slora_fedavg", "slora_lora_linear_ws_bytes", "slora_lora_linear_fwd",
            "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error", "slora_prof_enable",
-           "slora_prof_read"]
+           "slora_prof_read", "slora_frozen_linear_bf16"]
 
 
 class slora_config(ctypes.Structure):
@@ -68,6 +68,7 @@ def lib():
         L.slora_lora_linear_ws_bytes.restype = sz
         L.slora_lora_linear_fwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_lora_linear_bwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slora_frozen_linear_bf16.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
         L.slora_prof_enable.argtypes = [i32]
         L.slora_prof_read.argtypes = [vp, vp, vp]
         L.slora_strerror.argtypes = [i32]
@@ -169,6 +170,10 @@ def slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, x, W, bias, A, B, y, 
 def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, dA, dB, ws, ws_bytes, stream=None):
     _check(lib().slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, _p(x), _p(dy), _p(W), _p(A), _p(B),
                                        _p(dx), _p(dA), _p(dB), _p(ws), ws_bytes, _stream(stream)))
+
+
+def slora_frozen_linear_bf16(T, n_in, n_out, x, W, bias, y, stream=None):
+    _check(lib().slora_frozen_linear_bf16(T, n_in, n_out, _p(x), _p(W), _p(bias), _p(y), _stream(stream)))
 
 
 def slora_prof_enable(on):

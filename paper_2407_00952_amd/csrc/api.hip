@@ -705,6 +705,17 @@ int slora_lora_linear_fwd(int dtype, int T, int n_in, int n_out, int r, float al
     return launch_gemm(a, EPI_STORE, 32, st);
 }
 
+int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias, void *y,
+                             void *stream)
+{
+    if (T <= 0 || n_in <= 0 || n_out <= 0 || (n_in % 64) || !x || !W || !y) return SLORA_EINVAL;
+    if ((long long)T * (n_in > n_out ? n_in : n_out) > (1ll << 31) - 1) return SLORA_EINVAL;
+    if ((((uintptr_t)x) | ((uintptr_t)W) | ((uintptr_t)y)) & 15) return SLORA_EINVAL;
+    GemmArgs a = gemm_base((const bf16 *)x, n_in, (const bf16 *)W, T, n_out, n_in, (const bf16 *)bias, 0.f);
+    a.out0 = y;
+    return launch_gemm(a, EPI_STORE, 0, (hipStream_t)stream);
+}
+
 int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float alpha, const void *x, const void *dy,
                           const void *W, const float *A, const float *B, void *dx, float *dA, float *dB, void *ws,
                           size_t ws_bytes, void *stream)

@@ -82,24 +82,50 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
     if (NZ > 0 && has_z && tid < NZ * 8) zp = a.zmat[seg] + (size_t)lr * a.ldz + lc * 8;
     const int st_off = lr * ROWB + ((lc ^ (lr & 7)) << 4);     // (lr + 64p) & 7 == lr & 7
 
+    // Register prefetch: fully unrolled, compile-time indices only (anything less and the staging
+    // registers end up in scratch memory).
+#define GEMM_GLOAD(k0)                                                           \
+    _Pragma("unroll") for (int p = 0; p < 4; ++p) {                              \
+        xr[p] = *(const uint4 *)(xp[p] + (k0));                                  \
+        wr[p] = *(const uint4 *)(wp[p] + (k0));                                  \
+    }                                                                            \
+    if (NZ > 0 && zload) zr = *(const uint4 *)(zp + (k0));
+#define GEMM_LSTORE(buf)                                                         \
+    {                                                                            \
+        unsigned char *base_ = smem + (buf) * STAGE + st_off;                    \
+        _Pragma("unroll") for (int p = 0; p < 4; ++p) {                          \
+            *(uint4 *)(base_ + p * 64 * ROWB) = xr[p];                           \
+            *(uint4 *)(base_ + XB + p * 64 * ROWB) = wr[p];                      \
+        }                                                                        \
+        if (NZ > 0 && zload) *(uint4 *)(base_ + XB + WB) = zr;                   \
+    }
+#define GEMM_COMPUTE(buf)                                                                              \
+    {                                                                                                  \
+        const unsigned char *Xs = smem + (buf) * STAGE;                                                \
+        const unsigned char *Ws = Xs + XB;                                                             \
+        const unsigned char *Zs = Ws + WB;                                                             \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                             \
+            const int co = ((ks * 2 + g) ^ sw) << 4;                                                   \
+            bf16x8 af[4], bfr[2];                                                                      \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
+                af[i] = *(const bf16x8 *)(Xs + a_row + i * 32 * ROWB + co);                            \
+            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
+                bfr[j] = *(const bf16x8 *)(Ws + b_row + j * 32 * ROWB + co);                           \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
+                _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+            if (NZ > 0 && has_z) {                                                                     \
+                bf16x8 za = *(const bf16x8 *)(Xs + z_row + co);                                        \
+                _Pragma("unroll") for (int q = 0; q < NZ / 32; ++q) {                                  \
+                    bf16x8 zb = *(const bf16x8 *)(Zs + (q * 32 + r32) * ROWB + co);                    \
+                    zacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, zb, zacc[q], 0, 0, 0);       \
+                }                                                                                      \
+            }                                                                                          \
+        }                                                                                              \
+    }
+
     uint4 xr[4], wr[4], zr = {0, 0, 0, 0};
-    auto gload = [&](int k0) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            xr[p] = *(const uint4 *)(xp[p] + k0);
-            wr[p] = *(const uint4 *)(wp[p] + k0);
-        }
-        if (NZ > 0 && zp) zr = *(const uint4 *)(zp + k0);
-    };
-    auto lstore = [&](int buf) {
-        unsigned char *base = smem + buf * STAGE;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            *(uint4 *)(base + st_off + p * 64 * ROWB) = xr[p];
-            *(uint4 *)(base + XB + st_off + p * 64 * ROWB) = wr[p];
-        }
-        if (NZ > 0 && zp) *(uint4 *)(base + XB + WB + st_off) = zr;
-    };
+    const bool zload = (zp != nullptr);
 
     f32x16 acc[4][2];
 #pragma unroll
@@ -120,39 +146,20 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
     const int sw = r32 & 7;
 
     const int nk = a.K / BK;
-    gload(0);
-    lstore(0);
+    GEMM_GLOAD(0)
+    GEMM_LSTORE(0)
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload((kt + 1) * BK);
-        const unsigned char *Xs = smem + (kt & 1) * STAGE;
-        const unsigned char *Ws = Xs + XB;
-        const unsigned char *Zs = Ws + WB;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int co = ((ks * 2 + g) ^ sw) << 4;
-            bf16x8 af[4], bfr[2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8 *)(Xs + a_row + i * 32 * ROWB + co);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bfr[j] = *(const bf16x8 *)(Ws + b_row + j * 32 * ROWB + co);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-            if (NZ > 0 && has_z) {
-                bf16x8 za = *(const bf16x8 *)(Xs + z_row + co);
-#pragma unroll
-                for (int q = 0; q < NZ / 32; ++q) {
-                    bf16x8 zb = *(const bf16x8 *)(Zs + (q * 32 + r32) * ROWB + co);
-                    zacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, zb, zacc[q], 0, 0, 0);
-                }
-            }
-        }
-        if (kt + 1 < nk) lstore((kt + 1) & 1);
+    for (int kt = 0; kt < nk - 1; ++kt) {
+        GEMM_GLOAD((kt + 1) * BK)
+        GEMM_COMPUTE(kt & 1)
+        GEMM_LSTORE((kt + 1) & 1)
         __syncthreads();
     }
+    GEMM_COMPUTE((nk - 1) & 1)
+    __syncthreads();
+#undef GEMM_GLOAD
+#undef GEMM_LSTORE
+#undef GEMM_COMPUTE
 
     // ---- low-rank tail: acc += (zscale * z)[256,K2] . T[n,K2]^T -----------------------------
     if (NZ > 0 && has_z) {
