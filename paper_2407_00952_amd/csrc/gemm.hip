@@ -11,7 +11,9 @@
 // adapter-gradient kernels need it.
 //
 // Tiling: 256x256x64 block tile, 8 waves (2 x 4), wave tile 128x64 = 4x2 MFMA 32x32x16
-// tiles, double-buffered LDS with register prefetch, 16-byte XOR-swizzled LDS rows.
+// tiles; two LDS stages filled by asynchronous global->LDS copies (no staging registers),
+// 16-byte XOR-swizzled LDS rows so that both the copies and the MFMA operand reads are
+// bank-conflict free.
 #include "common.h"
 #include <vector>
 
@@ -40,13 +42,23 @@ __device__ __forceinline__ void store_one(const GemmArgs &a, int row, int col, f
     }
 }
 
+// asynchronous global -> LDS copy of 16 bytes per lane: the 64 lanes fill 1 KB starting at `lp`
+#define SL_GLDS(gp, lp)                                                                            \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gp),         \
+                                     (__attribute__((address_space(3))) void *)(lp), 16, 0, 0)
+#define SL_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)   // vmcnt(0): this wave's copies have landed
+
 template <int EPI, int NZ>
 __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ZB = NZ * ROWB, STAGE = XB + WB + ZB;
+    // two pipeline stages as separate objects, so that reads of one are not ordered behind the
+    // asynchronous copies into the other
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
     const int r32 = lane & 31, g = lane >> 5;
 
@@ -68,64 +80,21 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 
     const bool has_z = (NZ > 0) && (a.zmat[seg] != nullptr);
 
-    // ---- global -> register -> LDS assignment: 16-byte chunk lc of row lr + 64 p
-    const int lc = tid & 7, lr = tid >> 3;
+    // ---- global -> LDS: every wave copies 32 rows of the X tile and 32 rows of the W tile per
+    //      stage, 8 rows (1 KB) per instruction.  Lane l fills 16-byte slot l of the 1 KB chunk:
+    //      row l>>3, physical k-chunk l&7, which holds logical k-chunk (l&7) ^ (l>>3) (XOR swizzle).
+    const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
     const bf16 *xp[4], *wp[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        int row = min(m0 + lr + 64 * p, a.M - 1);
-        int n = min(n0 + lr + 64 * p, n_end - 1);
-        xp[p] = a.X + (size_t)row * a.ldx + lc * 8;
-        wp[p] = a.W + (size_t)n * a.ldw + lc * 8;
+        const int row = min(m0 + wave * 32 + p * 8 + lrow, a.M - 1);
+        const int n = min(n0 + wave * 32 + p * 8 + lrow, n_end - 1);
+        xp[p] = a.X + (size_t)row * a.ldx + lch * 8;
+        wp[p] = a.W + (size_t)n * a.ldw + lch * 8;
     }
-    const bf16 *zp = nullptr;
-    if (NZ > 0 && has_z && tid < NZ * 8) zp = a.zmat[seg] + (size_t)lr * a.ldz + lc * 8;
-    const int st_off = lr * ROWB + ((lc ^ (lr & 7)) << 4);     // (lr + 64p) & 7 == lr & 7
-
-    // Register prefetch: fully unrolled, compile-time indices only (anything less and the staging
-    // registers end up in scratch memory).
-#define GEMM_GLOAD(k0)                                                           \
-    _Pragma("unroll") for (int p = 0; p < 4; ++p) {                              \
-        xr[p] = *(const uint4 *)(xp[p] + (k0));                                  \
-        wr[p] = *(const uint4 *)(wp[p] + (k0));                                  \
-    }                                                                            \
-    if (NZ > 0 && zload) zr = *(const uint4 *)(zp + (k0));
-#define GEMM_LSTORE(buf)                                                         \
-    {                                                                            \
-        unsigned char *base_ = smem + (buf) * STAGE + st_off;                    \
-        _Pragma("unroll") for (int p = 0; p < 4; ++p) {                          \
-            *(uint4 *)(base_ + p * 64 * ROWB) = xr[p];                           \
-            *(uint4 *)(base_ + XB + p * 64 * ROWB) = wr[p];                      \
-        }                                                                        \
-        if (NZ > 0 && zload) *(uint4 *)(base_ + XB + WB) = zr;                   \
-    }
-#define GEMM_COMPUTE(buf)                                                                              \
-    {                                                                                                  \
-        const unsigned char *Xs = smem + (buf) * STAGE;                                                \
-        const unsigned char *Ws = Xs + XB;                                                             \
-        const unsigned char *Zs = Ws + WB;                                                             \
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                             \
-            const int co = ((ks * 2 + g) ^ sw) << 4;                                                   \
-            bf16x8 af[4], bfr[2];                                                                      \
-            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
-                af[i] = *(const bf16x8 *)(Xs + a_row + i * 32 * ROWB + co);                            \
-            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
-                bfr[j] = *(const bf16x8 *)(Ws + b_row + j * 32 * ROWB + co);                           \
-            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
-                _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
-            if (NZ > 0 && has_z) {                                                                     \
-                bf16x8 za = *(const bf16x8 *)(Xs + z_row + co);                                        \
-                _Pragma("unroll") for (int q = 0; q < NZ / 32; ++q) {                                  \
-                    bf16x8 zb = *(const bf16x8 *)(Zs + (q * 32 + r32) * ROWB + co);                    \
-                    zacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, zb, zacc[q], 0, 0, 0);       \
-                }                                                                                      \
-            }                                                                                          \
-        }                                                                                              \
-    }
-
-    uint4 xr[4], wr[4], zr = {0, 0, 0, 0};
-    const bool zload = (zp != nullptr);
+    const bool zload = (NZ > 0) && has_z && (wave < NZ / 8);
+    const bf16 *zp = zload ? a.zmat[seg] + (size_t)(wave * 8 + lrow) * a.ldz + lch * 8 : nullptr;
+    const int wofs = wave * 32 * ROWB;
 
     f32x16 acc[4][2];
 #pragma unroll
@@ -145,21 +114,68 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
     const int z_row = (wm * 128 + wn * 32 + r32) * ROWB;
     const int sw = r32 & 7;
 
+#define GEMM_ISSUE1(st, k0, p)                                        \
+    {                                                                 \
+        SL_GLDS(xp[p] + (k0), (st) + wofs + (p) * 1024);              \
+        SL_GLDS(wp[p] + (k0), (st) + XB + wofs + (p) * 1024);         \
+        if (NZ > 0 && (p) == 0 && zload) SL_GLDS(zp + (k0), (st) + XB + WB + wave * 1024); \
+    }
+#define GEMM_STEP(st, ks)                                                                              \
+    {                                                                                                  \
+        const unsigned char *Xs = (st), *Ws = (st) + XB, *Zs = (st) + XB + WB;                         \
+        const int co = (((ks) * 2 + g) ^ sw) << 4;                                                     \
+        bf16x8 af[4], bfr[2];                                                                          \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
+            af[i] = *(const bf16x8 *)(Xs + a_row + i * 32 * ROWB + co);                                \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
+            bfr[j] = *(const bf16x8 *)(Ws + b_row + j * 32 * ROWB + co);                               \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
+            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+        if (NZ > 0 && has_z) {                                                                         \
+            bf16x8 za = *(const bf16x8 *)(Xs + z_row + co);                                            \
+            _Pragma("unroll") for (int q = 0; q < NZ / 32; ++q) {                                      \
+                bf16x8 zb = *(const bf16x8 *)(Zs + (q * 32 + r32) * ROWB + co);                        \
+                zacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, zb, zacc[q], 0, 0, 0);           \
+            }                                                                                          \
+        }                                                                                              \
+    }
+    // one k-slab of 64: the copies for the next slab are issued a quarter at a time between the
+    // four MFMA groups so that no wave sits in the memory-issue queue while its MFMAs wait
+#define GEMM_PHASE(cur, nxt, k0, doload)                              \
+    {                                                                 \
+        if (doload) GEMM_ISSUE1(nxt, k0, 0)                           \
+        GEMM_STEP(cur, 0) __builtin_amdgcn_sched_barrier(0);          \
+        if (doload) GEMM_ISSUE1(nxt, k0, 1)                           \
+        GEMM_STEP(cur, 1) __builtin_amdgcn_sched_barrier(0);          \
+        if (doload) GEMM_ISSUE1(nxt, k0, 2)                           \
+        GEMM_STEP(cur, 2) __builtin_amdgcn_sched_barrier(0);          \
+        if (doload) GEMM_ISSUE1(nxt, k0, 3)                           \
+        GEMM_STEP(cur, 3) __builtin_amdgcn_sched_barrier(0);          \
+    }
+
     const int nk = a.K / BK;
-    GEMM_GLOAD(0)
-    GEMM_LSTORE(0)
+    GEMM_ISSUE1(st0, 0, 0) GEMM_ISSUE1(st0, 0, 1) GEMM_ISSUE1(st0, 0, 2) GEMM_ISSUE1(st0, 0, 3)
+    SL_WAIT_VM0();
     __syncthreads();
-    for (int kt = 0; kt < nk - 1; ++kt) {
-        GEMM_GLOAD((kt + 1) * BK)
-        GEMM_COMPUTE(kt & 1)
-        GEMM_LSTORE((kt + 1) & 1)
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+        GEMM_PHASE(st0, st1, (kt + 1) * BK, true)
+        SL_WAIT_VM0();
+        __syncthreads();
+        const bool more = kt + 2 < nk;
+        GEMM_PHASE(st1, st0, (kt + 2) * BK, more)
+        SL_WAIT_VM0();
         __syncthreads();
     }
-    GEMM_COMPUTE((nk - 1) & 1)
-    __syncthreads();
-#undef GEMM_GLOAD
-#undef GEMM_LSTORE
-#undef GEMM_COMPUTE
+    if (kt < nk) {
+        GEMM_PHASE(st0, st1, 0, false)
+        __syncthreads();
+    }
+#undef GEMM_ISSUE1
+#undef GEMM_STEP
+#undef GEMM_PHASE
+    unsigned char *smem = st0;
 
     // ---- low-rank tail: acc += (zscale * z)[256,K2] . T[n,K2]^T -----------------------------
     if (NZ > 0 && has_z) {
@@ -230,19 +246,11 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 template <int EPI, int NZ>
 int launch_t(const GemmArgs &a, hipStream_t st)
 {
-    constexpr int smem = 2 * (XB + WB + NZ * ROWB);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_kernel<EPI, NZ>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) { set_hip_error(e, "gemm smem attribute"); return -4; }
-        attr_set = true;
-    }
     const int tiles_n = ((a.seg_n + BN - 1) / BN) * a.nseg;
     const int tiles_m = (a.M + BM - 1) / BM;
     const int nb = tiles_m * tiles_n;
     const int grid = ((nb + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_kernel<EPI, NZ>), dim3(grid), dim3(NTHR), smem, st, a);
+    hipLaunchKernelGGL((gemm_kernel<EPI, NZ>), dim3(grid), dim3(NTHR), 0, st, a);
     SL_CHECK_LAUNCH("gemm");
     return 0;
 }
