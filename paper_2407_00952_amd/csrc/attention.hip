@@ -7,10 +7,12 @@
 // o / dO [T, d], lse [n_seq, H, S] fp32 in log2 units of the scaled scores, delta likewise.
 //
 // All three kernels use 4 wavefronts per block, each owning 32 rows (queries or keys), and
-// online-softmax tiles of 64.  Scores are produced with the lane owning one query (forward,
-// dQ) or one key (dK/dV), which makes the softmax statistics per-lane scalars and lets the
-// probabilities feed the next MFMA straight from registers.  Operands that must be read
-// along the token axis (V, K for dQ, Q and dO for dK/dV) are staged transposed in LDS.
+// online-softmax tiles of 64 staged in LDS by asynchronous global->LDS copies, double
+// buffered.  Scores are produced with the lane owning one query (forward, dQ) or one key
+// (dK/dV), which makes the softmax statistics per-lane scalars and lets the probabilities
+// feed the next MFMA straight from registers.  Operands that must be read along the token
+// axis (V, K for dQ, Q and dO for dK/dV) come from the same row-major tiles through the LDS
+// transpose read, so nothing is transposed in memory.
 // The backward is split into a dQ kernel and a dK/dV kernel so that no floating-point
 // atomics are needed and results are bit-reproducible.
 #include "common.h"
@@ -18,7 +20,14 @@
 namespace {
 
 constexpr float kScaleLog2 = 0.125f * 1.4426950408889634f;   // log2(e) / sqrt(64)
-constexpr int TP = 68;                                       // pitch (elements) of transposed tiles [64][64]
+constexpr int TILE_B = 64 * 128;                             // one 64-row x 64-column bf16 tile
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+#define AT_GLDS(gp, lp)                                                                            \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gp),         \
+                                     (__attribute__((address_space(3))) void *)(lp), 16, 0, 0)
+#define AT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
 __device__ __forceinline__ int swz128(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
@@ -30,71 +39,51 @@ __device__ __forceinline__ f32x16 zero16()
     return z;
 }
 
-__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b)
+// Asynchronous copy of a 64 x 64 bf16 tile (global pitch ld) into a swizzled row-major LDS tile.
+// Four waves, two 1 KB pieces (8 rows) each: lane l fills slot l = (row l>>3, physical chunk l&7).
+__device__ __forceinline__ void tile_copy_async(unsigned char *dst, const bf16 *src, int ld, int wave, int lane)
 {
-    bf16x8 r;
+    const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { r[i] = a[i]; r[4 + i] = b[i]; }
-    return r;
-}
-
-// 64 rows x 64 columns of bf16 from global (pitch ld) -> LDS row-major, 16-byte XOR swizzle
-__device__ __forceinline__ void stage_rows(unsigned char *dst, const bf16 *src, int ld, int tid)
-{
-#pragma unroll
-    for (int c = tid; c < 512; c += 256) {
-        const int row = c >> 3, ch = c & 7;
-        *(uint4 *)(dst + swz128(row, ch)) = *(const uint4 *)(src + (size_t)row * ld + ch * 8);
-    }
-}
-// the same tile -> LDS transposed: dst[col][row], pitch TP
-__device__ __forceinline__ void stage_cols(bf16 *dst, const bf16 *src, int ld, int tid)
-{
-#pragma unroll
-    for (int c = tid; c < 512; c += 256) {
-        const int row = c >> 3, ch = c & 7;
-        uint4 v = *(const uint4 *)(src + (size_t)row * ld + ch * 8);
-        const bf16 *e = (const bf16 *)&v;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dst[(ch * 8 + i) * TP + row] = e[i];
-    }
-}
-// both orientations from one global read
-__device__ __forceinline__ void stage_both(unsigned char *rm, bf16 *tr, const bf16 *src, int ld, int tid)
-{
-#pragma unroll
-    for (int c = tid; c < 512; c += 256) {
-        const int row = c >> 3, ch = c & 7;
-        uint4 v = *(const uint4 *)(src + (size_t)row * ld + ch * 8);
-        *(uint4 *)(rm + swz128(row, ch)) = v;
-        const bf16 *e = (const bf16 *)&v;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) tr[(ch * 8 + i) * TP + row] = e[i];
+    for (int p = 0; p < 2; ++p) {
+        const int r0 = (wave * 2 + p) * 8;
+        AT_GLDS(src + (size_t)(r0 + lrow) * ld + lch * 8, dst + r0 * 128);
     }
 }
 
-// A- or B-operand fragment: row (base + lane%32) of a swizzled row-major tile, k-step ks
+// MFMA operand fragment from a row-major tile: row (base + lane%32), k-step ks (16 columns)
 __device__ __forceinline__ bf16x8 frag_rm(const unsigned char *t, int row, int ks, int g)
 {
     return *(const bf16x8 *)(t + swz128(row, ks * 2 + g));
 }
-// fragment along the staged-transposed axis: 4 + 4 tokens at tok0 + 4g and tok0 + 8 + 4g
-__device__ __forceinline__ bf16x8 frag_tr(const bf16 *t, int col, int tok0, int g)
+
+// MFMA operand fragment along the ROW axis of a row-major tile (the transposed operand): lane
+// (m = lane%32, g = lane/32) receives column col0 + m at the 8 rows tok0 + 8h + 4g + e
+// (h = 0,1; e = 0..3), element index 4h + e.  Uses the LDS transpose read: inside each group of
+// 16 lanes, lane i receives element i%4 of the 8-byte pieces addressed by lanes i/4 + 4e.
+__device__ __forceinline__ bf16x8 frag_tr(const unsigned char *t, int col0, int tok0, int lane)
 {
-    const bf16 *p = t + col * TP + tok0 + 4 * g;
-    return cat4(*(const bf16x4 *)p, *(const bf16x4 *)(p + 8));
+    const int q = lane & 3, e = (lane >> 2) & 3, half = (lane >> 4) & 1, g = lane >> 5;
+    const int col = col0 + 16 * half + 4 * q;
+    const int row0 = tok0 + 4 * g + e, row1 = row0 + 8;
+    const unsigned char *a0 = t + row0 * 128 + (((col >> 3) ^ (row0 & 7)) << 4) + (col & 7) * 2;
+    const unsigned char *a1 = t + row1 * 128 + (((col >> 3) ^ (row1 & 7)) << 4) + (col & 7) * 2;
+    union { v4s s[2]; bf16x8 v; } u;
+    u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)a0);
+    u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)a1);
+    return u.v;
 }
 
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
                                                        float *__restrict__ lse, int S, int H)
 {
-    __shared__ __align__(16) unsigned char Ks[64 * 128];
-    __shared__ __align__(16) bf16 Vt[64 * TP];
+    __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
     const int qt = gridDim.x - 1 - blockIdx.x;          // longest rows first
     const int a = blockIdx.y, n = blockIdx.z;
     const int d = H * 64, ld = 3 * d;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
     const int qb = qt * 128 + wave * 32;
     const bool active = qb < S;
@@ -106,67 +95,75 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
         for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8 *)(base + (size_t)q * ld + ks * 16 + g * 8);
     }
     f32x16 oacc[2] = {zero16(), zero16()};
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY, l = 0.f;                       // running max (log2 units, scaled) and sum
     const int kv_end = min(S, qt * 128 + 128);
+    const int ntile = kv_end >> 6;
 
-    for (int k0 = 0; k0 < kv_end; k0 += 64) {
-        __syncthreads();
-        stage_rows(Ks, base + d + (size_t)k0 * ld, ld, tid);
-        stage_cols(Vt, base + 2 * d + (size_t)k0 * ld, ld, tid);
-        __syncthreads();
-        if (active && k0 <= qb + 31) {
-            f32x16 sacc[2] = {zero16(), zero16()};
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ks, mt * 32 + r32, ks, g), qf[ks],
-                                                                        sacc[mt], 0, 0, 0);
-            const bool need_mask = k0 + 63 > qb;
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = k0 + 32 * mt + 8 * (e >> 2) + 4 * g + (e & 3);
-                    float v = sacc[mt][e] * kScaleLog2;
-                    if (need_mask && key > q) v = -INFINITY;
-                    sacc[mt][e] = v;
-                    tmax = fmaxf(tmax, v);
-                }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m, tmax);
-            const float alpha = exp2f(m - m_new);
-            float psum = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = exp2f(sacc[mt][e] - m_new);
-                    sacc[mt][e] = p;
-                    psum += p;
-                }
-            psum += __shfl_xor(psum, 32, 64);
-            l = l * alpha + psum;
-            m = m_new;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    bf16x8 pb;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) pb[i] = f2bf(sacc[mt][8 * hh + i]);
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            frag_tr(Vt, 32 * dt + r32, 32 * mt + 16 * hh, g), pb, oacc[dt], 0, 0, 0);
-                }
-        }
+#define FWD_TILE(Ks, Vs, k0)                                                                           \
+    if (active && (k0) <= qb + 31) {                                                                   \
+        f32x16 sacc[2] = {zero16(), zero16()};                                                         \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                           \
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ks, mt * 32 + r32, ks, g),  \
+                                                                    qf[ks], sacc[mt], 0, 0, 0);        \
+        if ((k0) + 63 > qb) {                                                                          \
+            _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                           \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                       \
+                    const int key = (k0) + 32 * mt + 8 * (e >> 2) + 4 * g + (e & 3);                   \
+                    if (key > q) sacc[mt][e] = -INFINITY;                                              \
+                }                                                                                      \
+        }                                                                                              \
+        float tmax = sacc[0][0];                                                                       \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, sacc[mt][e]);            \
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));                                                  \
+        const float m_new = fmaxf(m, tmax * kScaleLog2);                                               \
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                         \
+        float psum = 0.f;                                                                              \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                           \
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mt][e], kScaleLog2, -m_new));         \
+                sacc[mt][e] = p;                                                                       \
+                psum += p;                                                                             \
+            }                                                                                          \
+        psum += __shfl_xor(psum, 32, 64);                                                              \
+        l = l * alpha + psum;                                                                          \
+        m = m_new;                                                                                     \
+        _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                               \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;                       \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
+            _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                         \
+                bf16x8 pb;                                                                             \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) pb[i] = f2bf(sacc[mt][8 * hh + i]);      \
+                _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                \
+                        frag_tr(Vs, 32 * dt, 32 * mt + 16 * hh, lane), pb, oacc[dt], 0, 0, 0);         \
+            }                                                                                          \
     }
+
+    const bf16 *kg = base + d, *vg = base + 2 * d;
+    tile_copy_async(K0, kg, ld, wave, lane);
+    tile_copy_async(V0, vg, ld, wave, lane);
+    AT_WAIT_VM0();
+    __syncthreads();
+    int j = 0;
+    for (; j + 2 <= ntile; j += 2) {
+        tile_copy_async(K1, kg + (size_t)(j + 1) * 64 * ld, ld, wave, lane);
+        tile_copy_async(V1, vg + (size_t)(j + 1) * 64 * ld, ld, wave, lane);
+        FWD_TILE(K0, V0, j * 64)
+        AT_WAIT_VM0();
+        __syncthreads();
+        if (j + 2 < ntile) {
+            tile_copy_async(K0, kg + (size_t)(j + 2) * 64 * ld, ld, wave, lane);
+            tile_copy_async(V0, vg + (size_t)(j + 2) * 64 * ld, ld, wave, lane);
+        }
+        FWD_TILE(K1, V1, (j + 1) * 64)
+        AT_WAIT_VM0();
+        __syncthreads();
+    }
+    if (j < ntile) FWD_TILE(K0, V0, j * 64)
+#undef FWD_TILE
+
     if (active) {
         const float inv = 1.0f / l;
         bf16 *orow = o + ((size_t)n * S + q) * d + a * 64;
@@ -190,13 +187,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict
                                                           const float *__restrict__ lse, float *__restrict__ delta,
                                                           bf16 *__restrict__ dqkv, int S, int H)
 {
-    __shared__ __align__(16) unsigned char Ks[64 * 128];
-    __shared__ __align__(16) unsigned char Vs[64 * 128];
-    __shared__ __align__(16) bf16 Kt[64 * TP];
+    __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
     const int qt = gridDim.x - 1 - blockIdx.x;
     const int a = blockIdx.y, n = blockIdx.z;
     const int d = H * 64, ld = 3 * d;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
     const int qb = qt * 128 + wave * 32;
     const bool active = qb < S;
@@ -221,44 +217,58 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict
     }
     f32x16 dqacc[2] = {zero16(), zero16()};
     const int kv_end = min(S, qt * 128 + 128);
+    const int ntile = kv_end >> 6;
 
-    for (int k0 = 0; k0 < kv_end; k0 += 64) {
-        __syncthreads();
-        stage_both(Ks, Kt, base + d + (size_t)k0 * ld, ld, tid);
-        stage_rows(Vs, base + 2 * d + (size_t)k0 * ld, ld, tid);
-        __syncthreads();
-        if (active && k0 <= qb + 31) {
-            const bool need_mask = k0 + 63 > qb;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                f32x16 sacc = zero16(), dpacc = zero16();
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ks, mt * 32 + r32, ks, g), qf[ks], sacc,
-                                                                    0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Vs, mt * 32 + r32, ks, g), dof[ks],
-                                                                     dpacc, 0, 0, 0);
-                }
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = k0 + 32 * mt + 8 * (e >> 2) + 4 * g + (e & 3);
-                    float p = exp2f(sacc[e] * kScaleLog2 - lse_q);
-                    if (need_mask && key > q) p = 0.f;
-                    sacc[e] = p * (dpacc[e] - dl);
-                }
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    bf16x8 dsb;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) dsb[i] = f2bf(sacc[8 * hh + i]);
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-                        dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            frag_tr(Kt, 32 * dt + r32, 32 * mt + 16 * hh, g), dsb, dqacc[dt], 0, 0, 0);
-                }
-            }
-        }
+#define DQ_TILE(Ks, Vs, k0)                                                                            \
+    if (active && (k0) <= qb + 31) {                                                                   \
+        const bool need_mask = (k0) + 63 > qb;                                                         \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt) {                                             \
+            f32x16 sacc = zero16(), dpacc = zero16();                                                  \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                         \
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ks, mt * 32 + r32, ks, g),      \
+                                                                qf[ks], sacc, 0, 0, 0);                \
+                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Vs, mt * 32 + r32, ks, g),     \
+                                                                 dof[ks], dpacc, 0, 0, 0);             \
+            }                                                                                          \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                           \
+                const int key = (k0) + 32 * mt + 8 * (e >> 2) + 4 * g + (e & 3);                       \
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -lse_q));                   \
+                if (need_mask && key > q) p = 0.f;                                                     \
+                sacc[e] = p * (dpacc[e] - dl);                                                         \
+            }                                                                                          \
+            _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                         \
+                bf16x8 dsb;                                                                            \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) dsb[i] = f2bf(sacc[8 * hh + i]);         \
+                _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
+                    dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                               \
+                        frag_tr(Ks, 32 * dt, 32 * mt + 16 * hh, lane), dsb, dqacc[dt], 0, 0, 0);       \
+            }                                                                                          \
+        }                                                                                              \
     }
+
+    const bf16 *kg = base + d, *vg = base + 2 * d;
+    tile_copy_async(K0, kg, ld, wave, lane);
+    tile_copy_async(V0, vg, ld, wave, lane);
+    AT_WAIT_VM0();
+    __syncthreads();
+    int j = 0;
+    for (; j + 2 <= ntile; j += 2) {
+        tile_copy_async(K1, kg + (size_t)(j + 1) * 64 * ld, ld, wave, lane);
+        tile_copy_async(V1, vg + (size_t)(j + 1) * 64 * ld, ld, wave, lane);
+        DQ_TILE(K0, V0, j * 64)
+        AT_WAIT_VM0();
+        __syncthreads();
+        if (j + 2 < ntile) {
+            tile_copy_async(K0, kg + (size_t)(j + 2) * 64 * ld, ld, wave, lane);
+            tile_copy_async(V0, vg + (size_t)(j + 2) * 64 * ld, ld, wave, lane);
+        }
+        DQ_TILE(K1, V1, (j + 1) * 64)
+        AT_WAIT_VM0();
+        __syncthreads();
+    }
+    if (j < ntile) DQ_TILE(K0, V0, j * 64)
+#undef DQ_TILE
+
     if (active) {
         bf16 *drow = dqkv + ((size_t)n * S + q) * ld + a * 64;
 #pragma unroll
@@ -281,18 +291,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
                                                            const float *__restrict__ delta,
                                                            bf16 *__restrict__ dqkv, int S, int H)
 {
-    __shared__ __align__(16) unsigned char Qs[64 * 128];
-    __shared__ __align__(16) unsigned char Ds[64 * 128];
-    __shared__ __align__(16) bf16 Qt[64 * TP];
-    __shared__ __align__(16) bf16 Dt[64 * TP];
-    __shared__ __align__(16) float lse_s[64];
-    __shared__ __align__(16) float dl_s[64];
+    __shared__ __attribute__((aligned(1024))) unsigned char Q0[TILE_B], D0[TILE_B], Q1[TILE_B], D1[TILE_B];
+    __shared__ __align__(16) float st0[128], st1[128];   // lse | delta of the 64 queries of a tile
     const int kvt = blockIdx.x;                          // keys kvt*128 ..: most work first
     const int a = blockIdx.y, n = blockIdx.z;
     const int d = H * 64, ld = 3 * d;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
     const bf16 *dbase = dout + (size_t)n * S * d + a * 64;
+    const float *lse_b = lse + ((size_t)n * H + a) * S, *dl_b = delta + ((size_t)n * H + a) * S;
     const int kb = kvt * 128 + wave * 32;
     const bool active = kb < S;
     const int key = kb + r32;
@@ -306,58 +314,85 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
         }
     }
     f32x16 dkacc[2] = {zero16(), zero16()}, dvacc[2] = {zero16(), zero16()};
+    const int q_first = kvt * 128;
+    const int ntile = (S - q_first) >> 6;
 
-    for (int q0 = kvt * 128; q0 < S; q0 += 64) {
-        __syncthreads();
-        stage_both(Qs, Qt, base + (size_t)q0 * ld, ld, tid);
-        stage_both(Ds, Dt, dbase + (size_t)q0 * d, d, tid);
-        if (tid < 64) lse_s[tid] = lse[((size_t)n * H + a) * S + q0 + tid];
-        else if (tid < 128) dl_s[tid - 64] = delta[((size_t)n * H + a) * S + q0 + tid - 64];
-        __syncthreads();
-        if (!active) continue;
-#pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            const int qs = q0 + 32 * st;
-            if (qs + 31 < kb) continue;                  // every query of the sub-tile precedes every key
-            const bool need_mask = qs < kb + 31;
-            f32x16 sacc = zero16(), dpacc = zero16();
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Qs, 32 * st + r32, ks, g), kf[ks], sacc, 0,
-                                                                0, 0);
-                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ds, 32 * st + r32, ks, g), vf[ks], dpacc, 0,
-                                                                 0, 0);
-            }
-            // lane = key column; element e = query row 8(e/4) + 4g + e%4 of the sub-tile
-#pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const int ql = 32 * st + 8 * e4 + 4 * g;
-                const f32x4 ls = *(const f32x4 *)(lse_s + ql);
-                const f32x4 dd = *(const f32x4 *)(dl_s + ql);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int e = 4 * e4 + i;
-                    float p = exp2f(sacc[e] * kScaleLog2 - ls[i]);
-                    if (need_mask && key > q0 + ql + i) p = 0.f;
-                    sacc[e] = p;
-                    dpacc[e] = p * (dpacc[e] - dd[i]);
-                }
-            }
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                bf16x8 pb, dsb;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) { pb[i] = f2bf(sacc[8 * hh + i]); dsb[i] = f2bf(dpacc[8 * hh + i]); }
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        frag_tr(Dt, 32 * dt + r32, 32 * st + 16 * hh, g), pb, dvacc[dt], 0, 0, 0);
-                    dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        frag_tr(Qt, 32 * dt + r32, 32 * st + 16 * hh, g), dsb, dkacc[dt], 0, 0, 0);
-                }
-            }
-        }
+#define DKV_TILE(Qs, Ds, stt, q0)                                                                      \
+    if (active) {                                                                                      \
+        _Pragma("unroll") for (int st = 0; st < 2; ++st) {                                             \
+            const int qs = (q0) + 32 * st;                                                             \
+            if (qs + 31 >= kb) {                                                                       \
+                const bool need_mask = qs < kb + 31;                                                   \
+                f32x16 sacc = zero16(), dpacc = zero16();                                              \
+                _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                     \
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Qs, 32 * st + r32, ks, g),  \
+                                                                    kf[ks], sacc, 0, 0, 0);            \
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ds, 32 * st + r32, ks, g), \
+                                                                     vf[ks], dpacc, 0, 0, 0);          \
+                }                                                                                      \
+                _Pragma("unroll") for (int e4 = 0; e4 < 4; ++e4) {                                     \
+                    const int ql = 32 * st + 8 * e4 + 4 * g;                                           \
+                    const f32x4 ls = *(const f32x4 *)((stt) + ql);                                     \
+                    const f32x4 dd = *(const f32x4 *)((stt) + 64 + ql);                                \
+                    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                    \
+                        const int e = 4 * e4 + i;                                                      \
+                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i]));           \
+                        if (need_mask && key > (q0) + ql + i) p = 0.f;                                 \
+                        sacc[e] = p;                                                                   \
+                        dpacc[e] = p * (dpacc[e] - dd[i]);                                             \
+                    }                                                                                  \
+                }                                                                                      \
+                _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                     \
+                    bf16x8 pb, dsb;                                                                    \
+                    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                    \
+                        pb[i] = f2bf(sacc[8 * hh + i]);                                                \
+                        dsb[i] = f2bf(dpacc[8 * hh + i]);                                              \
+                    }                                                                                  \
+                    _Pragma("unroll") for (int dt = 0; dt < 2; ++dt) {                                 \
+                        dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                           \
+                            frag_tr(Ds, 32 * dt, 32 * st + 16 * hh, lane), pb, dvacc[dt], 0, 0, 0);    \
+                        dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                           \
+                            frag_tr(Qs, 32 * dt, 32 * st + 16 * hh, lane), dsb, dkacc[dt], 0, 0, 0);   \
+                    }                                                                                  \
+                }                                                                                      \
+            }                                                                                          \
+        }                                                                                              \
     }
+    // per-query statistics travel through a register so that their LDS store (which has to wait
+    // for the load) sits after the MFMA work of the current tile
+    float stat = 0.f;
+#define DKV_ISSUE(Qs, Ds, q0)                                                                          \
+    {                                                                                                  \
+        tile_copy_async(Qs, base + (size_t)(q0) * ld, ld, wave, lane);                                 \
+        tile_copy_async(Ds, dbase + (size_t)(q0) * d, d, wave, lane);                                  \
+        if (tid < 64) stat = lse_b[(q0) + tid];                                                        \
+        else if (tid < 128) stat = dl_b[(q0) + tid - 64];                                              \
+    }
+#define DKV_COMMIT(stt) if (tid < 128) (stt)[tid] = stat;
+
+    DKV_ISSUE(Q0, D0, q_first)
+    DKV_COMMIT(st0)
+    AT_WAIT_VM0();
+    __syncthreads();
+    int j = 0;
+    for (; j + 2 <= ntile; j += 2) {
+        DKV_ISSUE(Q1, D1, q_first + (j + 1) * 64)
+        DKV_TILE(Q0, D0, st0, q_first + j * 64)
+        DKV_COMMIT(st1)
+        AT_WAIT_VM0();
+        __syncthreads();
+        const bool more = j + 2 < ntile;
+        if (more) DKV_ISSUE(Q0, D0, q_first + (j + 2) * 64)
+        DKV_TILE(Q1, D1, st1, q_first + (j + 1) * 64)
+        if (more) DKV_COMMIT(st0)
+        AT_WAIT_VM0();
+        __syncthreads();
+    }
+    if (j < ntile) DKV_TILE(Q0, D0, st0, q_first + j * 64)
+#undef DKV_ISSUE
+#undef DKV_COMMIT
+#undef DKV_TILE
+
     if (active) {
         bf16 *krow = dqkv + ((size_t)n * S + key) * ld + d + a * 64;
         bf16 *vrow = krow + d;

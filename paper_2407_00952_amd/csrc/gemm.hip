@@ -23,22 +23,43 @@ constexpr int BM = 256, BN = 256, BK = 64, NTHR = 512;
 constexpr int ROWB = BK * 2;                 // bytes per LDS row (one k-slab of a tile row)
 constexpr int XB = BM * ROWB, WB = BN * ROWB;
 
+// Epilogue on 8 consecutive columns of one output row (v already holds acc + bias).
 template <int EPI>
-__device__ __forceinline__ void store_one(const GemmArgs &a, int row, int col, float v)
+__device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, float (&v)[8])
 {
     const size_t o = (size_t)row * a.ldo + col;
     if (EPI == EPI_STORE) {
-        ((bf16 *)a.out0)[o] = f2bf(v);
+        bf16x8 w;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i]);
+        *(bf16x8 *)((bf16 *)a.out0 + o) = w;
     } else if (EPI == EPI_RESID) {
-        v += ((const float *)a.aux)[o];
-        if (a.out0) ((float *)a.out0)[o] = v;
-        if (a.out1) ((bf16 *)a.out1)[o] = f2bf(v);
+        const float4 r0 = *(const float4 *)((const float *)a.aux + o);
+        const float4 r1 = *(const float4 *)((const float *)a.aux + o + 4);
+        v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w;
+        v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+        if (a.out0) {
+            *(float4 *)((float *)a.out0 + o) = make_float4(v[0], v[1], v[2], v[3]);
+            *(float4 *)((float *)a.out0 + o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        }
+        if (a.out1) {
+            bf16x8 w;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i]);
+            *(bf16x8 *)((bf16 *)a.out1 + o) = w;
+        }
     } else if (EPI == EPI_GELU) {
-        ((bf16 *)a.out0)[o] = f2bf(v);
-        ((bf16 *)a.out1)[o] = f2bf(gelu_fwd(v));
+        bf16x8 wf, wg;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { wf[i] = f2bf(v[i]); wg[i] = f2bf(gelu_fwd(v[i])); }
+        *(bf16x8 *)((bf16 *)a.out0 + o) = wf;
+        *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
     } else {   // EPI_DGELU
-        float f = bf2f(((const bf16 *)a.aux)[o]);
-        ((bf16 *)a.out0)[o] = f2bf(v * gelu_bwd(f));
+        const bf16x8 f = *(const bf16x8 *)((const bf16 *)a.aux + o);
+        bf16x8 w;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * gelu_bwd(bf2f(f[i])));
+        *(bf16x8 *)((bf16 *)a.out0 + o) = w;
     }
 }
 
@@ -225,20 +246,40 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
         }
     }
 
-    // ---- epilogue: lane holds column (lane & 31) of each 32x32 tile, rows 8(e/4) + 4g + e%4
+    // ---- epilogue.  A lane holds column (lane & 31) of each 32x32 tile, rows 8(e/4) + 4g + e%4:
+    //      each wave transposes its tiles through a private LDS strip (32 rows x 64 columns fp32)
+    //      so that global memory sees 16-byte accesses, 8 rows x 128..256 contiguous bytes per
+    //      instruction.  Only the owning wave touches its strip, so no block barrier is needed.
+    constexpr int EP = 72;                               // strip pitch in floats (bank-conflict free)
+    if (NZ > 0 && has_z) __syncthreads();                // the z tile in st0 has been consumed
+    float *stg = (float *)((wave < 4 ? st0 : st1) + (wave & 3) * (32 * EP * 4));
+    const int er = lane >> 3, ec = (lane & 7) * 8;
+    const int gcol = n0 + wn * 64 + ec;
+    float bias8[8];
+    {
+        bf16x8 b8;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = n0 + wn * 64 + j * 32 + r32;
-        if (col >= n_end) continue;
-        const float bias = a.bias ? bf2f(a.bias[col]) : 0.0f;
+        for (int i = 0; i < 8; ++i) b8[i] = f2bf(0.f);
+        if (a.bias && gcol < n_end) b8 = *(const bf16x8 *)(a.bias + gcol);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int rb = m0 + wm * 128 + i * 32 + 4 * g;
+        for (int i = 0; i < 8; ++i) bias8[i] = bf2f(b8[i]);
+    }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = rb + 8 * (e >> 2) + (e & 3);
-                if (row < a.M) store_one<EPI>(a, row, col, acc[i][j][e] + bias);
-            }
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stg[(8 * (e >> 2) + 4 * g + (e & 3)) * EP + j * 32 + r32] = acc[i][j][e];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int rl = it * 8 + er;
+            const float4 p0 = *(const float4 *)(stg + rl * EP + ec);
+            const float4 p1 = *(const float4 *)(stg + rl * EP + ec + 4);
+            float v[8] = {p0.x + bias8[0], p0.y + bias8[1], p0.z + bias8[2], p0.w + bias8[3],
+                          p1.x + bias8[4], p1.y + bias8[5], p1.z + bias8[6], p1.w + bias8[7]};
+            const int row = m0 + wm * 128 + i * 32 + rl;
+            if (row < a.M && gcol < n_end) store_row8<EPI>(a, row, gcol, v);
         }
     }
 }
@@ -327,7 +368,7 @@ int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st)
 static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K % BK) != 0 || a.nseg < 1 || a.nseg > 3 ||
-        a.nseg * a.seg_n != a.N || (a.ldx % 8) || (a.ldw % 8))
+        a.nseg * a.seg_n != a.N || (a.ldx % 8) || (a.ldw % 8) || (a.seg_n % 8) || (a.ldo % 8))
         return -1;
     if (nz > 0 && (a.K2 < 16 || a.K2 > nz || (a.K2 % 16) || (a.ldt % 8) || (a.ldz % 8))) return -1;
     switch (epi) {

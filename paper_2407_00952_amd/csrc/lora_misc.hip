@@ -12,39 +12,59 @@
 
 namespace {
 
-constexpr int GR_ROWS = 256;   // token rows per block (64 per wavefront)
+constexpr int GR_ROWS = 128;   // token rows per block (32 per wavefront)
+constexpr int GR_COLS = 512;   // columns per block: 8 per lane, 16-byte loads
 
 template <int R>
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__restrict__ X, int ldx, int C,
                                                                 const bf16 *__restrict__ Y, int ldy, int r, int T,
                                                                 float *__restrict__ partials)
 {
-    __shared__ float red[3][R][256];
+    __shared__ float red[3][R][GR_COLS];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c0 = blockIdx.x * 256 + lane * 4;
+    const int c0 = blockIdx.x * GR_COLS + lane * 8;
     const int chunk = blockIdx.y;
-    const int t0 = chunk * GR_ROWS + wave * 64;
-    const int t1 = min(t0 + 64, T);
-    float acc[4][R];
+    const int t0 = chunk * GR_ROWS + wave * 32;
+    const int t1 = min(t0 + 32, T);
+    float acc[8][R];
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc)
+    for (int cc = 0; cc < 8; ++cc)
 #pragma unroll
         for (int j = 0; j < R; ++j) acc[cc][j] = 0.f;
-    const bool colok = c0 < C;   // C % 4 == 0
-    for (int t = t0; t < t1; ++t) {
-        float x[4] = {0.f, 0.f, 0.f, 0.f};
-        if (colok) {
-            bf16x4 xv = *(const bf16x4 *)(X + (size_t)t * ldx + c0);
+    const bool colok = c0 < C;   // C % 8 == 0
+    int t = t0;
+    // four rows per trip: the four 16-byte loads are in flight together
+    for (; t + 4 <= t1; t += 4) {
+        bf16x8 xv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = bf2f(xv[i]);
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xv[u][i] = f2bf(0.f);
+            if (colok) xv[u] = *(const bf16x8 *)(X + (size_t)(t + u) * ldx + c0);
         }
-        const bf16 *yr = Y + (size_t)t * ldy;      // wave-uniform address
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bf16 *yr = Y + (size_t)(t + u) * ldy;      // wave-uniform address
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const float y = (j < r) ? bf2f(yr[j]) : 0.f;
+#pragma unroll
+                for (int cc = 0; cc < 8; ++cc) acc[cc][j] = fmaf(bf2f(xv[u][cc]), y, acc[cc][j]);
+            }
+        }
+    }
+    for (; t < t1; ++t) {
+        bf16x8 xv;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xv[i] = f2bf(0.f);
+        if (colok) xv = *(const bf16x8 *)(X + (size_t)t * ldx + c0);
+        const bf16 *yr = Y + (size_t)t * ldy;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const float y = (j < r) ? bf2f(yr[j]) : 0.f;
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) acc[cc][j] = fmaf(x[cc], y, acc[cc][j]);
+            for (int cc = 0; cc < 8; ++cc) acc[cc][j] = fmaf(bf2f(xv[cc]), y, acc[cc][j]);
         }
     }
     // fixed order over the four wavefronts: wave 0 adds the partial sums of waves 1, 2, 3
@@ -52,37 +72,53 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__re
 #pragma unroll
         for (int j = 0; j < R; ++j)
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) red[wave - 1][j][lane * 4 + cc] = acc[cc][j];
+            for (int cc = 0; cc < 8; ++cc) red[wave - 1][j][cc * 64 + lane] = acc[cc][j];
     }
     __syncthreads();
     if (wave == 0 && colok) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             if (j < r) {
-                float s[4];
+                float s[8];
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
+                for (int cc = 0; cc < 8; ++cc) {
                     s[cc] = acc[cc][j];
-                    s[cc] += red[0][j][lane * 4 + cc];
-                    s[cc] += red[1][j][lane * 4 + cc];
-                    s[cc] += red[2][j][lane * 4 + cc];
+                    s[cc] += red[0][j][cc * 64 + lane];
+                    s[cc] += red[1][j][cc * 64 + lane];
+                    s[cc] += red[2][j][cc * 64 + lane];
                 }
-                *(float4 *)(partials + ((size_t)chunk * r + j) * C + c0) = make_float4(s[0], s[1], s[2], s[3]);
+                float *dst = partials + ((size_t)chunk * r + j) * C + c0;
+                *(float4 *)dst = make_float4(s[0], s[1], s[2], s[3]);
+                *(float4 *)(dst + 4) = make_float4(s[4], s[5], s[6], s[7]);
             }
         }
     }
 }
 
+// out[j, c] = sum over chunks, in a fixed order: each of the 4 wavefronts of a block sums a
+// contiguous quarter of the chunks in increasing order, then the four are added in order.
 __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float *__restrict__ partials, int nchunk, int r,
                                                                int C, float *__restrict__ out, int out_is_rxC)
 {
-    const int idx = blockIdx.x * 256 + threadIdx.x;     // over r*C, c fastest
-    if (idx >= r * C) return;
-    const int j = idx / C, c = idx - j * C;
+    __shared__ float red[3][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int idx = blockIdx.x * 64 + lane;              // over r*C, c fastest
+    const bool ok = idx < r * C;
+    const int j = ok ? idx / C : 0, c = ok ? idx - j * C : 0;
+    const int per = (nchunk + 3) >> 2;
+    const int k0 = wave * per, k1 = min(k0 + per, nchunk);
     float s = 0.f;
-    for (int k = 0; k < nchunk; ++k) s += partials[((size_t)k * r + j) * C + c];
-    if (out_is_rxC) out[(size_t)j * C + c] = s;
-    else out[(size_t)c * r + j] = s;
+    if (ok)
+        for (int k = k0; k < k1; ++k) s += partials[((size_t)k * r + j) * C + c];
+    if (wave > 0) red[wave - 1][lane] = s;
+    __syncthreads();
+    if (wave == 0 && ok) {
+        s += red[0][lane];
+        s += red[1][lane];
+        s += red[2][lane];
+        if (out_is_rxC) out[(size_t)j * C + c] = s;
+        else out[(size_t)c * r + j] = s;
+    }
 }
 
 __global__ __launch_bounds__(256) void sgd_kernel(float *__restrict__ p, const float *__restrict__ g, float lr,
@@ -185,9 +221,9 @@ size_t lora_grad_partial_floats(int T, int C)
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
                      float *out, int out_is_rxC, hipStream_t st)
 {
-    if (T <= 0 || C <= 0 || (C % 4) || (ldx % 4) || r < 1 || r > 16) return -1;
+    if (T <= 0 || C <= 0 || (C % 8) || (ldx % 8) || r < 1 || r > 16) return -1;
     const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
-    dim3 grid((C + 255) / 256, nchunk);
+    dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
     if (r <= 4)
         hipLaunchKernelGGL((lora_grad_partial_kernel<4>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
     else if (r <= 8)
@@ -195,7 +231,7 @@ int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int 
     else
         hipLaunchKernelGGL((lora_grad_partial_kernel<16>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
     SL_CHECK_LAUNCH("lora_grad_partial");
-    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((r * C + 255) / 256), dim3(256), 0, st, partials, nchunk, r, C,
+    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
                        out, out_is_rxC);
     SL_CHECK_LAUNCH("lora_grad_reduce");
     return 0;
