@@ -71,7 +71,7 @@ struct BlockWs {
     size_t bz[SLORA_NPROJ], bt[SLORA_NPROJ];   // backward (o, fc, pr): B^T [32,out], A^T [in,16]
     size_t bz_qkv, bt_qkv;                     // backward, fused q|k|v: block-diagonal B^T [NZ,3d], A^T [d,K2]
     // saved between forward and backward
-    size_t h_in, stats1, qkv, o, lse, h_mid, stats2, f, u, u2, g;
+    size_t h_in, stats1, qkv, o, o_lo, lse, h_mid, stats2, f, u, u2, g;
     size_t zs[SLORA_NPROJ];
 };
 
@@ -154,6 +154,7 @@ void plan_workspace(slora_ctx *c)
         b.stats1 = take(8 * T);
         b.qkv = take(2 * T * 3 * d);
         b.o = take(2 * T * d);
+        b.o_lo = take(2 * T * d);
         b.lse = take(4 * T * H);
         b.h_mid = take(4 * T * d);
         b.stats2 = take(8 * T);
@@ -451,7 +452,8 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
                 }
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? 32 : 0, st))) return rc;
         }
-        if ((rc = launch_attn_fwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<float>(c, b.lse), c->n_seq, c->S, c->H,
+        if ((rc = launch_attn_fwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<bf16>(c, b.o_lo), at<float>(c, b.lse), c->n_seq,
+                                  c->S, c->H,
                                   st)))
             return rc;
         // h' = h + o Wo^T + bo (+ adapter)
@@ -566,7 +568,7 @@ int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, vo
         }
         // attention backward
         bf16 *dqkv = at<bf16>(c, c->t_dqkv);
-        if ((rc = launch_attn_bwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), dob, at<float>(c, b.lse),
+        if ((rc = launch_attn_bwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<bf16>(c, b.o_lo), dob, at<float>(c, b.lse),
                                   at<float>(c, c->t_delta), dqkv, c->n_seq, c->S, c->H, st)))
             return rc;
         // du = [dq dk dv] Wqkv (+ adapters): one GEMM with contraction 3d

@@ -76,7 +76,8 @@ __device__ __forceinline__ bf16x8 frag_tr(const unsigned char *t, int col0, int 
 
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
-                                                       float *__restrict__ lse, int S, int H)
+                                                       bf16 *__restrict__ o_lo, float *__restrict__ lse, int S,
+                                                       int H)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
     const int qt = gridDim.x - 1 - blockIdx.x;          // longest rows first
@@ -95,7 +96,10 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
         for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8 *)(base + (size_t)q * ld + ks * 16 + g * 8);
     }
     f32x16 oacc[2] = {zero16(), zero16()};
-    float m = -INFINITY, l = 0.f;                       // running max (log2 units, scaled) and sum
+    // running max (log2 units, scaled); l = sum of the probabilities (for the log-sum-exp the backward
+    // uses), lh = sum of the bf16-ROUNDED probabilities that actually enter the P.V product: dividing by
+    // lh makes O an exact convex combination of V rows, which the backward's rowsum(dO*O) relies on
+    float m = -INFINITY, l = 0.f, lh = 0.f;
     const int kv_end = min(S, qt * 128 + 128);
     const int ntile = kv_end >> 6;
 
@@ -129,16 +133,22 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
         psum += __shfl_xor(psum, 32, 64);                                                              \
         l = l * alpha + psum;                                                                          \
         m = m_new;                                                                                     \
+        float hsum = 0.f;                                                                              \
         _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                               \
             _Pragma("unroll") for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;                       \
         _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
             _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                         \
                 bf16x8 pb;                                                                             \
-                _Pragma("unroll") for (int i = 0; i < 8; ++i) pb[i] = f2bf(sacc[mt][8 * hh + i]);      \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                        \
+                    pb[i] = f2bf(sacc[mt][8 * hh + i]);                                                \
+                    hsum += bf2f(pb[i]);                                                               \
+                }                                                                                      \
                 _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
                     oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                \
                         frag_tr(Vs, 32 * dt, 32 * mt + 16 * hh, lane), pb, oacc[dt], 0, 0, 0);         \
             }                                                                                          \
+        hsum += __shfl_xor(hsum, 32, 64);                                                              \
+        lh = lh * alpha + hsum;                                                                        \
     }
 
     const bf16 *kg = base + d, *vg = base + 2 * d;
@@ -165,16 +175,21 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
 #undef FWD_TILE
 
     if (active) {
-        const float inv = 1.0f / l;
-        bf16 *orow = o + ((size_t)n * S + q) * d + a * 64;
+        const float inv = 1.0f / lh;
+        const size_t ooff = ((size_t)n * S + q) * d + a * 64;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
-                bf16x4 w;
+                bf16x4 w, wl;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w[i] = f2bf(oacc[dt][4 * e4 + i] * inv);
-                *(bf16x4 *)(orow + 32 * dt + 8 * e4 + 4 * g) = w;
+                for (int i = 0; i < 4; ++i) {
+                    const float v = oacc[dt][4 * e4 + i] * inv;
+                    w[i] = f2bf(v);
+                    wl[i] = f2bf(v - bf2f(w[i]));       // second bf16 term: o + o_lo carries ~16 bits
+                }
+                *(bf16x4 *)(o + ooff + 32 * dt + 8 * e4 + 4 * g) = w;
+                if (o_lo) *(bf16x4 *)(o_lo + ooff + 32 * dt + 8 * e4 + 4 * g) = wl;
             }
         if (g == 0) lse[((size_t)n * H + a) * S + q] = m + log2f(l);
     }
@@ -183,6 +198,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O), which the dK/dV kernel reads afterwards)
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ o,
+                                                          const bf16 *__restrict__ o_lo,
                                                           const bf16 *__restrict__ dout,
                                                           const float *__restrict__ lse, float *__restrict__ delta,
                                                           bf16 *__restrict__ dqkv, int S, int H)
@@ -202,14 +218,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict
     float lse_q = 0.f, dl = 0.f;
     if (active) {
         const bf16 *orow = o + ((size_t)n * S + q) * d + a * 64;
+        const bf16 *lrow = o_lo + ((size_t)n * S + q) * d + a * 64;
         const bf16 *drow = dout + ((size_t)n * S + q) * d + a * 64;
+        // delta = rowsum(dO * O) with O to ~16 bits (o + o_lo): when the value rows of a head share a
+        // large common component, dP - delta cancels it, and a delta built from bf16 O alone would not
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             qf[ks] = *(const bf16x8 *)(base + (size_t)q * ld + ks * 16 + g * 8);
             dof[ks] = *(const bf16x8 *)(drow + ks * 16 + g * 8);
             bf16x8 of = *(const bf16x8 *)(orow + ks * 16 + g * 8);
+            bf16x8 ol = *(const bf16x8 *)(lrow + ks * 16 + g * 8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dl += bf2f(dof[ks][i]) * bf2f(of[i]);
+            for (int i = 0; i < 8; ++i) dl += bf2f(dof[ks][i]) * (bf2f(of[i]) + bf2f(ol[i]));
         }
         dl += __shfl_xor(dl, 32, 64);
         lse_q = lse[((size_t)n * H + a) * S + q];
@@ -285,7 +305,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict
 
 // ------------------------------------------------------------------------------------------
 // dK, dV: each wavefront owns 32 keys and walks the query tiles that can see them
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
                                                            const bf16 *__restrict__ dout,
                                                            const float *__restrict__ lse,
                                                            const float *__restrict__ delta,
@@ -414,21 +434,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
 
 }  // namespace
 
-int launch_attn_fwd(const bf16 *qkv, bf16 *o, float *lse, int n_seq, int S, int H, hipStream_t st)
+int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st)
 {
     if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return -1;
     dim3 grid((S + 127) / 128, H, n_seq);
-    hipLaunchKernelGGL(attn_fwd_kernel, grid, dim3(256), 0, st, qkv, o, lse, S, H);
+    hipLaunchKernelGGL(attn_fwd_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, lse, S, H);
     SL_CHECK_LAUNCH("attn_fwd");
     return 0;
 }
 
-int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *dout, const float *lse, float *delta, bf16 *dqkv,
-                    int n_seq, int S, int H, hipStream_t st)
+int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16 *dout, const float *lse,
+                    float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st)
 {
     if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return -1;
     dim3 grid((S + 127) / 128, H, n_seq);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, dout, lse, delta, dqkv, S, H);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, dout, lse, delta, dqkv, S, H);
     SL_CHECK_LAUNCH("attn_bwd_dq");
     hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, dim3(256), 0, st, qkv, dout, lse, delta, dqkv, S, H);
     SL_CHECK_LAUNCH("attn_bwd_dkv");

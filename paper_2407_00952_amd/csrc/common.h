@@ -76,9 +76,9 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather /*null unless bl
 int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16 *gamma,
                   const float *dres_f32, const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16,
                   const ClientTable *scatter, int T, int d, hipStream_t st);
-int launch_attn_fwd(const bf16 *qkv, bf16 *o, float *lse, int n_seq, int S, int H, hipStream_t st);
-int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *dout, const float *lse, float *delta,
-                    bf16 *dqkv, int n_seq, int S, int H, hipStream_t st);
+int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st);
+int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16 *dout, const float *lse,
+                    float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st);
 // G[c, j] = sum_t X[t, c] * Y[t, j], j < r; written transposed ([r, C]) when out_is_rxC.
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T,
                      float *partials, float *out, int out_is_rxC, hipStream_t st);

@@ -160,13 +160,16 @@ def _sampled_parity(cfg, seqs):
     _, Ys, _, grads = gpu_round(cfg, inp, clients=sub_clients, dY=sub_dY, server=srv)
     for i, n in enumerate(seqs):
         assert np.array_equal(Ys[i], Y[n])
-    worst = 0.0
+    errs = {}
     for l in range(cfg.n_blocks):
         for p in cfg.lora_proj:
-            ea, eb = relerr(grads[l][p][0], tot[l][p][0]), relerr(grads[l][p][1], tot[l][p][1])
-            worst = max(worst, ea, eb)
-            assert ea <= BF16_TOL and eb <= BF16_TOL, (l, p, ea, eb)
-    say("   adapter gradients on the sampled sequences: worst %.2e" % worst)
+            errs["dA[%d,%s]" % (l, p)] = relerr(grads[l][p][0], tot[l][p][0])
+            errs["dB[%d,%s]" % (l, p)] = relerr(grads[l][p][1], tot[l][p][1])
+    vals = np.array(list(errs.values()))
+    top = sorted(errs.items(), key=lambda kv: -kv[1])[:3]
+    say("   adapter gradients on the sampled sequences: median %.2e, worst %s"
+        % (np.median(vals), ", ".join("%s=%.2e" % kv for kv in top)))
+    assert vals.max() <= BF16_TOL, top
     srv.close()
 
 
@@ -178,9 +181,9 @@ def test_workload3_sampled():
 
 def test_workload4_sampled():
     say("workload 4:", synth.CONFIGS[4])
-    _sampled_parity(synth.CONFIGS[4], [13])
+    _sampled_parity(synth.CONFIGS[4], [13, 2, 27])
 
 
 def test_workload5_sampled():
     say("workload 5:", synth.CONFIGS[5])
-    _sampled_parity(synth.CONFIGS[5], [50])
+    _sampled_parity(synth.CONFIGS[5], [50, 9])
