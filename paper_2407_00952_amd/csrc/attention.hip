@@ -75,7 +75,7 @@ __device__ __forceinline__ bf16x8 frag_tr(const unsigned char *t, int col0, int 
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
+__global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
                                                        bf16 *__restrict__ o_lo, float *__restrict__ lse, int S,
                                                        int H)
 {
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
 
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O), which the dK/dV kernel reads afterwards)
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ o,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ o,
                                                           const bf16 *__restrict__ o_lo,
                                                           const bf16 *__restrict__ dout,
                                                           const float *__restrict__ lse, float *__restrict__ delta,

@@ -23,9 +23,34 @@ constexpr int BM = 256, BN = 256, BK = 64, NTHR = 512;
 constexpr int ROWB = BK * 2;                 // bytes per LDS row (one k-slab of a tile row)
 constexpr int XB = BM * ROWB, WB = BN * ROWB;
 
+// Epilogue operands that come from global memory (the residual stream, or the pre-GELU activation),
+// fetched one 32-row strip ahead of their use so that their latency hides behind the LDS transpose.
+struct AuxRow {
+    float4 r0, r1;       // EPI_RESID: 8 fp32 residual values
+    bf16x8 f;            // EPI_DGELU: 8 bf16 pre-activations
+};
+
+template <int EPI>
+__device__ __forceinline__ void load_aux(const GemmArgs &a, int row, int col, bool ok, AuxRow &x)
+{
+    if (EPI == EPI_RESID) {
+        x.r0 = make_float4(0.f, 0.f, 0.f, 0.f);
+        x.r1 = x.r0;
+        if (ok) {
+            const float *p = (const float *)a.aux + (size_t)row * a.ldo + col;
+            x.r0 = *(const float4 *)p;
+            x.r1 = *(const float4 *)(p + 4);
+        }
+    } else if (EPI == EPI_DGELU) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x.f[i] = f2bf(0.f);
+        if (ok) x.f = *(const bf16x8 *)((const bf16 *)a.aux + (size_t)row * a.ldo + col);
+    }
+}
+
 // Epilogue on 8 consecutive columns of one output row (v already holds acc + bias).
 template <int EPI>
-__device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, float (&v)[8])
+__device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, float (&v)[8], const AuxRow &x)
 {
     const size_t o = (size_t)row * a.ldo + col;
     if (EPI == EPI_STORE) {
@@ -34,10 +59,8 @@ __device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, 
         for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i]);
         *(bf16x8 *)((bf16 *)a.out0 + o) = w;
     } else if (EPI == EPI_RESID) {
-        const float4 r0 = *(const float4 *)((const float *)a.aux + o);
-        const float4 r1 = *(const float4 *)((const float *)a.aux + o + 4);
-        v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w;
-        v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+        v[0] += x.r0.x; v[1] += x.r0.y; v[2] += x.r0.z; v[3] += x.r0.w;
+        v[4] += x.r1.x; v[5] += x.r1.y; v[6] += x.r1.z; v[7] += x.r1.w;
         if (a.out0) {
             *(float4 *)((float *)a.out0 + o) = make_float4(v[0], v[1], v[2], v[3]);
             *(float4 *)((float *)a.out0 + o + 4) = make_float4(v[4], v[5], v[6], v[7]);
@@ -55,10 +78,9 @@ __device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, 
         *(bf16x8 *)((bf16 *)a.out0 + o) = wf;
         *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
     } else {   // EPI_DGELU
-        const bf16x8 f = *(const bf16x8 *)((const bf16 *)a.aux + o);
         bf16x8 w;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * gelu_bwd(bf2f(f[i])));
+        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * gelu_bwd(bf2f(x.f[i])));
         *(bf16x8 *)((bf16 *)a.out0 + o) = w;
     }
 }
@@ -264,8 +286,22 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int i = 0; i < 8; ++i) bias8[i] = bf2f(b8[i]);
     }
+    AuxRow aux[2][4];
+    const int row_base = m0 + wm * 128 + er;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int row = row_base + it * 8;
+        load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[0][it]);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+        if (i + 1 < 4) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = row_base + (i + 1) * 32 + it * 8;
+                load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[(i + 1) & 1][it]);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -279,7 +315,7 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
             float v[8] = {p0.x + bias8[0], p0.y + bias8[1], p0.z + bias8[2], p0.w + bias8[3],
                           p1.x + bias8[4], p1.y + bias8[5], p1.z + bias8[6], p1.w + bias8[7]};
             const int row = m0 + wm * 128 + i * 32 + rl;
-            if (row < a.M && gcol < n_end) store_row8<EPI>(a, row, gcol, v);
+            if (row < a.M && gcol < n_end) store_row8<EPI>(a, row, gcol, v, aux[i & 1][it]);
         }
     }
 }
