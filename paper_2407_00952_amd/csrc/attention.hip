@@ -96,10 +96,19 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
         for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8 *)(base + (size_t)q * ld + ks * 16 + g * 8);
     }
     f32x16 oacc[2] = {zero16(), zero16()};
-    // running max (log2 units, scaled); l = sum of the probabilities (for the log-sum-exp the backward
-    // uses), lh = sum of the bf16-ROUNDED probabilities that actually enter the P.V product: dividing by
-    // lh makes O an exact convex combination of V rows, which the backward's rowsum(dO*O) relies on
-    float m = -INFINITY, l = 0.f, lh = 0.f;
+    // The softmax is VALU-bound at head size 64, so the per-element work is kept to one FMA, one
+    // exp2 and a share of a max and of a bf16 pack:
+    //  * the row sum is taken by the matrix core: an all-ones A operand against the bf16
+    //    probabilities gives sum_k P[k][q] in every row of `lacc`; only element 0 is kept consistent
+    //    (rescaled), the other rows are never read.  Summing the ROUNDED probabilities also makes O an
+    //    exact convex combination of V rows, which the backward's rowsum(dO*O) relies on.
+    //  * the running maximum m (log2 units, scaled) is only raised when a tile exceeds it by more
+    //    than 8, so most tiles skip the rescaling of the accumulators; p <= 2^8 meanwhile.
+    f32x16 lacc = zero16();
+    bf16x8 ones;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones[i] = f2bf(1.0f);
+    float m = -INFINITY;
     const int kv_end = min(S, qt * 128 + 128);
     const int ntile = kv_end >> 6;
 
@@ -120,35 +129,25 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
         float tmax = sacc[0][0];                                                                       \
         _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
             _Pragma("unroll") for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, sacc[mt][e]);            \
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));                                                  \
-        const float m_new = fmaxf(m, tmax * kScaleLog2);                                               \
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                         \
-        float psum = 0.f;                                                                              \
-        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                           \
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mt][e], kScaleLog2, -m_new));         \
-                sacc[mt][e] = p;                                                                       \
-                psum += p;                                                                             \
-            }                                                                                          \
-        psum += __shfl_xor(psum, 32, 64);                                                              \
-        l = l * alpha + psum;                                                                          \
-        m = m_new;                                                                                     \
-        float hsum = 0.f;                                                                              \
-        _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                               \
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;                       \
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * kScaleLog2;                                     \
+        if (__builtin_amdgcn_ballot_w64(tmax > m + 8.0f) != 0) {                                       \
+            const float m_new = fmaxf(m, tmax);                                                        \
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                     \
+            m = m_new;                                                                                 \
+            lacc[0] *= alpha;                                                                          \
+            _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                           \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;                   \
+        }                                                                                              \
         _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
             _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                         \
                 bf16x8 pb;                                                                             \
-                _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                        \
-                    pb[i] = f2bf(sacc[mt][8 * hh + i]);                                                \
-                    hsum += bf2f(pb[i]);                                                               \
-                }                                                                                      \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i)                                          \
+                    pb[i] = f2bf(__builtin_amdgcn_exp2f(fmaf(sacc[mt][8 * hh + i], kScaleLog2, -m)));  \
+                lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, lacc, 0, 0, 0);               \
                 _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
                     oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                \
                         frag_tr(Vs, 32 * dt, 32 * mt + 16 * hh, lane), pb, oacc[dt], 0, 0, 0);         \
             }                                                                                          \
-        hsum += __shfl_xor(hsum, 32, 64);                                                              \
-        lh = lh * alpha + hsum;                                                                        \
     }
 
     const bf16 *kg = base + d, *vg = base + 2 * d;
@@ -175,6 +174,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
 #undef FWD_TILE
 
     if (active) {
+        const float lh = lacc[0];
         const float inv = 1.0f / lh;
         const size_t ooff = ((size_t)n * S + q) * d + a * 64;
 #pragma unroll
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
                 *(bf16x4 *)(o + ooff + 32 * dt + 8 * e4 + 4 * g) = w;
                 if (o_lo) *(bf16x4 *)(o_lo + ooff + 32 * dt + 8 * e4 + 4 * g) = wl;
             }
-        if (g == 0) lse[((size_t)n * H + a) * S + q] = m + log2f(l);
+        if (g == 0) lse[((size_t)n * H + a) * S + q] = m + log2f(lh);
     }
 }
 

@@ -108,8 +108,20 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float *__re
     const int per = (nchunk + 3) >> 2;
     const int k0 = wave * per, k1 = min(k0 + per, nchunk);
     float s = 0.f;
-    if (ok)
-        for (int k = k0; k < k1; ++k) s += partials[((size_t)k * r + j) * C + c];
+    if (ok) {
+        const float *src = partials + (size_t)j * C + c;
+        const size_t step = (size_t)r * C;
+        int k = k0;
+        // eight loads in flight, added in increasing chunk order
+        for (; k + 8 <= k1; k += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(k + u) * step];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; k < k1; ++k) s += src[(size_t)k * step];
+    }
     if (wave > 0) red[wave - 1][lane] = s;
     __syncthreads();
     if (wave == 0 && ok) {
