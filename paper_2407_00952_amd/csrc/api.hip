@@ -471,7 +471,7 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
         if ((rc = launch_ln_fwd(at<float>(c, b.h_mid), nullptr, nullptr, fz[SLORA_LN2_G], fz[SLORA_LN2_B],
                                 c->cfg.ln_eps, u2, at<float>(c, b.stats2), T, d, st)))
             return rc;
-        // f = u2 Wfc^T + bfc (+ adapter); g = GELU(f)
+        // f = u2 Wfc^T + bfc (+ adapter); g = GELU(f); the slot `f` keeps GELU'(f), all the backward needs
         bf16 *g = at<bf16>(c, b.g ? b.g : c->t_g);
         {
             GemmArgs a = gemm_base(u2, d, fz[SLORA_WFC], T, dff, d, fz[SLORA_BFC], c->s);

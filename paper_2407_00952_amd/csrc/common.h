@@ -35,6 +35,14 @@ static __device__ __forceinline__ float gelu_sig(float f)
     return __builtin_amdgcn_rcpf(1.0f + __expf(-u2));
 }
 static __device__ __forceinline__ float gelu_fwd(float f) { return f * gelu_sig(f); }
+// value and derivative from one sigmoid evaluation
+static __device__ __forceinline__ void gelu_fwd_bwd(float f, float &gval, float &gder)
+{
+    const float c2 = 1.5957691216057308f;
+    const float sg = gelu_sig(f);
+    gval = f * sg;
+    gder = sg + gval * (1.0f - sg) * c2 * (1.0f + 3.0f * 0.044715f * f * f);
+}
 static __device__ __forceinline__ float gelu_bwd(float f)
 {
     const float c2 = 1.5957691216057308f;

@@ -23,11 +23,11 @@ constexpr int BM = 256, BN = 256, BK = 64, NTHR = 512;
 constexpr int ROWB = BK * 2;                 // bytes per LDS row (one k-slab of a tile row)
 constexpr int XB = BM * ROWB, WB = BN * ROWB;
 
-// Epilogue operands that come from global memory (the residual stream, or the pre-GELU activation),
+// Epilogue operands that come from global memory (the residual stream, or the saved GELU derivative),
 // fetched one 32-row strip ahead of their use so that their latency hides behind the LDS transpose.
 struct AuxRow {
     float4 r0, r1;       // EPI_RESID: 8 fp32 residual values
-    bf16x8 f;            // EPI_DGELU: 8 bf16 pre-activations
+    bf16x8 f;            // EPI_DGELU: 8 bf16 values of GELU'(f) saved by the forward
 };
 
 template <int EPI>
@@ -74,13 +74,19 @@ __device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, 
     } else if (EPI == EPI_GELU) {
         bf16x8 wf, wg;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { wf[i] = f2bf(v[i]); wg[i] = f2bf(gelu_fwd(v[i])); }
+        for (int i = 0; i < 8; ++i) {
+            // out0 keeps GELU'(f) (all the backward needs of f), out1 = GELU(f)
+            float gv, gd;
+            gelu_fwd_bwd(v[i], gv, gd);
+            wf[i] = f2bf(gd);
+            wg[i] = f2bf(gv);
+        }
         *(bf16x8 *)((bf16 *)a.out0 + o) = wf;
         *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
     } else {   // EPI_DGELU
         bf16x8 w;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * gelu_bwd(bf2f(x.f[i])));
+        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * bf2f(x.f[i]));   // aux holds GELU'(f)
         *(bf16x8 *)((bf16 *)a.out0 + o) = w;
     }
 }
