@@ -120,7 +120,13 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
     const int per_xcd = (nb + 7) >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= nb) return;
-    const int tm = logical / tiles_n, tn = logical % tiles_n;
+    // inside an XCD's range the tiles are walked in panels of 4 row tiles, column by column, so the
+    // 32 tiles in flight on an XCD form a 4 x 8 patch: each X row tile and each W column tile is
+    // fetched into that L2 once per patch instead of W being re-streamed for every pair of row tiles
+    constexpr int PANEL = 4;
+    const int pidx = logical / (PANEL * tiles_n), prem = logical - pidx * (PANEL * tiles_n);
+    const int prow = min(PANEL, tiles_m - pidx * PANEL);
+    const int tn = prem / prow, tm = pidx * PANEL + prem - tn * prow;
     const int seg = tn / tiles_n_seg;
     const int tns = tn % tiles_n_seg;
     const int n0 = seg * a.seg_n + tns * BN;
