@@ -3,95 +3,142 @@
 //  * LoRA gradients (SplitLoRA Sec. III-B step a3: "derive the server-side LoRA adapters'
 //    gradients"): with ps = s (dy B) and zs = s (x A^T) spilled by the GEMMs,
 //        dA = ps^T x   [r,in]        dB = dy^T zs   [out,r]
-//    Both are G[c,j] = sum_t X[t,c] Y[t,j] with a tall X [T,C] and a skinny Y [T,r]: one
-//    streaming pass over X (HBM-bound), per-chunk partial sums, then a fixed-order
-//    reduction over chunks -- no floating-point atomics, so results are reproducible.
+//    Both are G[c,j] = sum_t X[t,c] Y[t,j] with a tall X [T,C] and a skinny Y [T,16]: one
+//    streaming pass over X (HBM-bound) feeding MFMAs whose operands are read along the token
+//    axis with the LDS transpose read, per-chunk partial sums, then a fixed-order reduction
+//    over chunks -- no floating-point atomics, so results are reproducible.  Y must have 16
+//    readable columns per row (the spilled rank-space activations are padded with zeros).
 //  * SGD (Eq. 4-5): p = fmaf(-lr, g, p).
 //  * FedAvg (Sec. III-B step b2, Eq. 8-9): acc = fmaf(w_i, x_i[j], acc), i = 0..K-1.
 #include "common.h"
 
 namespace {
 
-constexpr int GR_ROWS = 128;   // token rows per block (32 per wavefront)
-constexpr int GR_COLS = 512;   // columns per block: 8 per lane, 16-byte loads
+constexpr int GR_ROWS = 512;   // token rows per block: 8 tiles of 64
+constexpr int GR_COLS = 256;   // columns of X per block: 64 per wavefront (two MFMA row tiles)
+constexpr int GX_TILE = 64 * GR_COLS * 2;   // bytes of one 64-token X tile in LDS
 
-template <int R>
+typedef short v4s_t __attribute__((ext_vector_type(4)));
+#define LG_GLDS(gp, lp)                                                                            \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gp),         \
+                                     (__attribute__((address_space(3))) void *)(lp), 16, 0, 0)
+#define LG_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
+
+// LDS transpose read (see attention.hip): lane (m = lane%32, g = lane/32) gets column col0 + m of the
+// 8 rows tok0 + 8h + 4g + e of a row-major tile.  X tile: 512-byte rows, 64-byte granules XOR-swizzled
+// with the row so that the four rows one read touches fall into different banks.
+__device__ __forceinline__ bf16x8 xfrag_tr(const unsigned char *t, int col0, int tok0, int lane)
+{
+    const int q = lane & 3, e = (lane >> 2) & 3, half = (lane >> 4) & 1, g = lane >> 5;
+    const int col = col0 + 16 * half + 4 * q;
+    const int row0 = tok0 + 4 * g + e, row1 = row0 + 8;
+    const unsigned char *a0 = t + row0 * 512 + ((((col >> 3)) ^ ((row0 & 7) << 2)) << 4) + (col & 7) * 2;
+    const unsigned char *a1 = t + row1 * 512 + ((((col >> 3)) ^ ((row1 & 7) << 2)) << 4) + (col & 7) * 2;
+    union { v4s_t s[2]; bf16x8 v; } u;
+    u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)a0);
+    u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)a1);
+    return u.v;
+}
+// Y tile: [64 tokens][16] bf16, 32-byte rows, no swizzle; every lane group reads columns 0..15 (the
+// MFMA columns 16..31 then hold copies that are never stored)
+__device__ __forceinline__ bf16x8 yfrag_tr(const unsigned char *t, int tok0, int lane)
+{
+    const int q = lane & 3, e = (lane >> 2) & 3, g = lane >> 5;
+    const int row0 = tok0 + 4 * g + e, row1 = row0 + 8;
+    union { v4s_t s[2]; bf16x8 v; } u;
+    u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)(t + row0 * 32 + q * 8));
+    u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)(t + row1 * 32 + q * 8));
+    return u.v;
+}
+
+// partial[chunk][j][c] = sum over the chunk's tokens of X[t,c] * Y[t,j]  on the matrix cores:
+// D[m = c][n = j] += X^T[c][t] * Y[t][j], both operands read along the token axis with the LDS
+// transpose read from row-major tiles that asynchronous copies (X) and plain loads (Y) fill.
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__restrict__ X, int ldx, int C,
                                                                 const bf16 *__restrict__ Y, int ldy, int r, int T,
                                                                 float *__restrict__ partials)
 {
-    __shared__ float red[3][R][GR_COLS];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c0 = blockIdx.x * GR_COLS + lane * 8;
+    __shared__ __attribute__((aligned(1024))) unsigned char X0[GX_TILE], X1[GX_TILE];
+    __shared__ __attribute__((aligned(16))) unsigned char Y0[64 * 32], Y1[64 * 32];
+    const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c_blk = blockIdx.x * GR_COLS;
     const int chunk = blockIdx.y;
-    const int t0 = chunk * GR_ROWS + wave * 32;
-    const int t1 = min(t0 + 32, T);
-    float acc[8][R];
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc)
-#pragma unroll
-        for (int j = 0; j < R; ++j) acc[cc][j] = 0.f;
-    const bool colok = c0 < C;   // C % 8 == 0
-    int t = t0;
-    // four rows per trip: the four 16-byte loads are in flight together
-    for (; t + 4 <= t1; t += 4) {
-        bf16x8 xv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) xv[u][i] = f2bf(0.f);
-            if (colok) xv[u] = *(const bf16x8 *)(X + (size_t)(t + u) * ldx + c0);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const bf16 *yr = Y + (size_t)(t + u) * ldy;      // wave-uniform address
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const float y = (j < r) ? bf2f(yr[j]) : 0.f;
-#pragma unroll
-                for (int cc = 0; cc < 8; ++cc) acc[cc][j] = fmaf(bf2f(xv[u][cc]), y, acc[cc][j]);
-            }
-        }
+    const int t_begin = chunk * GR_ROWS;
+    const int ntile = (min(T, t_begin + GR_ROWS) - t_begin + 63) >> 6;
+    const bool wave_ok = c_blk + wave * 64 < C;          // C is a multiple of 64
+
+    // X copy: each instruction moves 2 token rows x 512 B; lane l -> row l>>5, physical 16-byte slot
+    // l&31 which holds logical slot (l&31) ^ ((row&7)<<2).  32 instructions per tile, 8 per wave.
+    const int xrow = lane >> 5, xslot = lane & 31;
+    // Y copy: 128 threads x 16 B per tile, through a register (committed to LDS after the MFMA work)
+    uint4 yreg = {0, 0, 0, 0};
+#define LG_ISSUE(Xs, jj)                                                                           \
+    {                                                                                              \
+        const int t0_ = t_begin + (jj) * 64;                                                       \
+        if (tid < 128) {                                                                           \
+            const int tr_ = t0_ + (tid >> 1);                                                      \
+            yreg = make_uint4(0, 0, 0, 0);                                                         \
+            if (tr_ < T) yreg = *(const uint4 *)(Y + (size_t)tr_ * ldy + (tid & 1) * 8);           \
+        }                                                                                          \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) {                                            \
+            const int row_ = (wave * 8 + p) * 2 + xrow;                                            \
+            const int tg_ = min(t0_ + row_, T - 1);                                                \
+            const int lslot_ = xslot ^ ((row_ & 7) << 2);                                          \
+            const int cg_ = min(c_blk + lslot_ * 8, C - 8);                                        \
+            LG_GLDS(X + (size_t)tg_ * ldx + cg_, (Xs) + (wave * 8 + p) * 1024);                    \
+        }                                                                                          \
     }
-    for (; t < t1; ++t) {
-        bf16x8 xv;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) xv[i] = f2bf(0.f);
-        if (colok) xv = *(const bf16x8 *)(X + (size_t)t * ldx + c0);
-        const bf16 *yr = Y + (size_t)t * ldy;
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            const float y = (j < r) ? bf2f(yr[j]) : 0.f;
-#pragma unroll
-            for (int cc = 0; cc < 8; ++cc) acc[cc][j] = fmaf(bf2f(xv[cc]), y, acc[cc][j]);
-        }
+#define LG_COMMIT(Ys) if (tid < 128) *(uint4 *)((Ys) + (tid >> 1) * 32 + (tid & 1) * 16) = yreg;
+#define LG_TILE(Xs, Ys)                                                                            \
+    if (wave_ok) {                                                                                 \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                         \
+            const bf16x8 yb = yfrag_tr(Ys, ks * 16, lane);                                         \
+            _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                       \
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                 \
+                    xfrag_tr(Xs, wave * 64 + mt * 32, ks * 16, lane), yb, acc[mt], 0, 0, 0);       \
+        }                                                                                          \
     }
-    // fixed order over the four wavefronts: wave 0 adds the partial sums of waves 1, 2, 3
-    if (wave > 0) {
+
+    f32x16 acc[2];
 #pragma unroll
-        for (int j = 0; j < R; ++j)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int cc = 0; cc < 8; ++cc) red[wave - 1][j][cc * 64 + lane] = acc[cc][j];
-    }
+        for (int e = 0; e < 16; ++e) acc[mt][e] = 0.f;
+
+    LG_ISSUE(X0, 0)
+    LG_COMMIT(Y0)
+    LG_WAIT_VM0();
     __syncthreads();
-    if (wave == 0 && colok) {
+    int j = 0;
+    for (; j + 2 <= ntile; j += 2) {
+        LG_ISSUE(X1, j + 1)
+        LG_TILE(X0, Y0)
+        LG_COMMIT(Y1)
+        LG_WAIT_VM0();
+        __syncthreads();
+        const bool more = j + 2 < ntile;
+        if (more) LG_ISSUE(X0, j + 2)
+        LG_TILE(X1, Y1)
+        if (more) LG_COMMIT(Y0)
+        LG_WAIT_VM0();
+        __syncthreads();
+    }
+    if (j < ntile) LG_TILE(X0, Y0)
+#undef LG_ISSUE
+#undef LG_COMMIT
+#undef LG_TILE
+
+    // lane holds column j = lane%32 of D, rows c = 8(e/4) + 4g + e%4 of each 32-row tile
+    if (wave_ok && r32 < r) {
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            if (j < r) {
-                float s[8];
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int cc = 0; cc < 8; ++cc) {
-                    s[cc] = acc[cc][j];
-                    s[cc] += red[0][j][cc * 64 + lane];
-                    s[cc] += red[1][j][cc * 64 + lane];
-                    s[cc] += red[2][j][cc * 64 + lane];
-                }
-                float *dst = partials + ((size_t)chunk * r + j) * C + c0;
-                *(float4 *)dst = make_float4(s[0], s[1], s[2], s[3]);
-                *(float4 *)(dst + 4) = make_float4(s[4], s[5], s[6], s[7]);
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int c = c_blk + wave * 64 + mt * 32 + 8 * e4 + 4 * g;
+                *(float4 *)(partials + ((size_t)chunk * r + r32) * C + c) =
+                    make_float4(acc[mt][4 * e4], acc[mt][4 * e4 + 1], acc[mt][4 * e4 + 2], acc[mt][4 * e4 + 3]);
             }
-        }
     }
 }
 
@@ -233,15 +280,10 @@ size_t lora_grad_partial_floats(int T, int C)
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
                      float *out, int out_is_rxC, hipStream_t st)
 {
-    if (T <= 0 || C <= 0 || (C % 8) || (ldx % 8) || r < 1 || r > 16) return -1;
+    if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || r < 1 || r > 16) return -1;
     const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
     dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
-    if (r <= 4)
-        hipLaunchKernelGGL((lora_grad_partial_kernel<4>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
-    else if (r <= 8)
-        hipLaunchKernelGGL((lora_grad_partial_kernel<8>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
-    else
-        hipLaunchKernelGGL((lora_grad_partial_kernel<16>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
+    hipLaunchKernelGGL(lora_grad_partial_kernel, grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
     SL_CHECK_LAUNCH("lora_grad_partial");
     hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
                        out, out_is_rxC);
