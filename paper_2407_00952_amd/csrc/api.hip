@@ -67,9 +67,9 @@ struct AdapterBind { float *A, *B, *dA, *dB; };
 struct BlockWs {
     // persistent: transposed frozen weights and bf16 adapter shadows
     size_t WqkvT, WoT, WfcT, WprT;
-    size_t fz[SLORA_NPROJ], ft[SLORA_NPROJ];   // forward: down-projection [32,in], up-projection [out,16]
-    size_t bz[SLORA_NPROJ], bt[SLORA_NPROJ];   // backward (o, fc, pr): B^T [32,out], A^T [in,16]
-    size_t bz_qkv, bt_qkv;                     // backward, fused q|k|v: block-diagonal B^T [NZ,3d], A^T [d,K2]
+    size_t fz[SLORA_NPROJ], ft[SLORA_NPROJ];   // forward: down-projection [16,in], up-projection [out,32]
+    size_t bz[SLORA_NPROJ], bt[SLORA_NPROJ];   // backward (o, fc, pr): B^T [16,out], A^T [in,32]
+    size_t bz_qkv, bt_qkv;                     // backward, fused q|k|v: block-diagonal B^T [16n,3d], A^T [d,K2P]
     // saved between forward and backward
     size_t h_in, stats1, qkv, o, o_lo, lse, h_mid, stats2, f, u, u2, g;
     size_t zs[SLORA_NPROJ];
@@ -82,7 +82,7 @@ struct slora_ctx {
     int d, H, dff, L, r, S, maxT;
     float s;
     uint32_t mask;
-    int n_qkv, qkv_idx[3], nz_qkv, k2_qkv;     // adapters among q,k,v and their slot in the fused operands
+    int n_qkv, qkv_idx[3], nz_qkv, k2_qkv, k2p_qkv;   // adapters among q,k,v and their slot in the fused operands
     std::vector<std::array<const bf16 *, SLORA_NFROZEN>> frozen;
     std::vector<std::array<AdapterBind, SLORA_NPROJ>> adapters;
     std::vector<BlockWs> bw;
@@ -131,17 +131,17 @@ void plan_workspace(slora_ctx *c)
             if (!adapted(c, p)) continue;
             int n_in, n_out;
             proj_shape(c, p, n_in, n_out);
-            b.fz[p] = take(2 * 32 * (size_t)n_in);
-            b.ft[p] = take(2 * (size_t)n_out * SL_RP);
+            b.fz[p] = take(2 * 16 * (size_t)n_in);
+            b.ft[p] = take(2 * (size_t)n_out * 32);
             if (p >= SLORA_PROJ_O) {
-                b.bz[p] = take(2 * 32 * (size_t)n_out);
-                b.bt[p] = take(2 * (size_t)n_in * SL_RP);
+                b.bz[p] = take(2 * 16 * (size_t)n_out);
+                b.bt[p] = take(2 * (size_t)n_in * 32);
             }
         }
         b.bz_qkv = b.bt_qkv = 0;
         if (c->n_qkv) {
             b.bz_qkv = take(2 * (size_t)c->nz_qkv * 3 * d);
-            b.bt_qkv = take(2 * d * (size_t)c->k2_qkv);
+            b.bt_qkv = take(2 * d * (size_t)c->k2p_qkv);
         }
     }
     c->shadow_end = off;
@@ -197,18 +197,18 @@ void build_tables(slora_ctx *c)
             int n_in, n_out;
             proj_shape(c, p, n_in, n_out);
             // forward operands
-            c->h_cast.push_back({ab.A, at<bf16>(c, b.fz[p]), c->r, n_in, 0, n_in, 32, n_in});
-            c->h_cast.push_back({ab.B, at<bf16>(c, b.ft[p]), n_out, c->r, 0, SL_RP, n_out, SL_RP});
+            c->h_cast.push_back({ab.A, at<bf16>(c, b.fz[p]), c->r, n_in, 0, n_in, 16, n_in});
+            c->h_cast.push_back({ab.B, at<bf16>(c, b.ft[p]), n_out, c->r, 0, 32, n_out, 32});
             // backward operands
             if (p >= SLORA_PROJ_O) {
-                c->h_cast.push_back({ab.B, at<bf16>(c, b.bz[p]), n_out, c->r, 1, n_out, 32, n_out});
-                c->h_cast.push_back({ab.A, at<bf16>(c, b.bt[p]), c->r, n_in, 1, SL_RP, n_in, SL_RP});
+                c->h_cast.push_back({ab.B, at<bf16>(c, b.bz[p]), n_out, c->r, 1, n_out, 16, n_out});
+                c->h_cast.push_back({ab.A, at<bf16>(c, b.bt[p]), c->r, n_in, 1, 32, n_in, 32});
             } else {
                 const int idx = c->qkv_idx[p];
                 // rows 16 idx .. of the block-diagonal B^T, columns p d ..; other entries stay zero
                 c->h_cast.push_back({ab.B, at<bf16>(c, b.bz_qkv) + (size_t)16 * idx * 3 * c->d + (size_t)p * c->d,
                                      n_out, c->r, 1, 3 * c->d, SL_RP, n_out});
-                c->h_cast.push_back({ab.A, at<bf16>(c, b.bt_qkv) + 16 * idx, c->r, n_in, 1, c->k2_qkv, n_in, SL_RP});
+                c->h_cast.push_back({ab.A, at<bf16>(c, b.bt_qkv) + 16 * idx, c->r, n_in, 1, c->k2p_qkv, n_in, SL_RP});
             }
             c->h_sgd.push_back({ab.A, ab.dA, c->r * n_in, 0});
             c->h_sgd.push_back({ab.B, ab.dB, n_out * c->r, 0});
@@ -275,7 +275,7 @@ GemmArgs gemm_base(const bf16 *X, int ldx, const bf16 *W, int M, int N, int K, c
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.X = X; a.ldx = ldx; a.W = W; a.ldw = K; a.M = M; a.N = N; a.K = K;
-    a.nseg = 1; a.seg_n = N; a.bias = bias; a.ldo = N; a.zscale = s; a.K2 = 16; a.ldz = K; a.ldt = 16;
+    a.nseg = 1; a.seg_n = N; a.bias = bias; a.ldo = N; a.zscale = s; a.K2 = 16; a.ldz = K; a.ldt = 32;
     return a;
 }
 
@@ -343,8 +343,9 @@ int slora_create(const slora_config *cfg, slora_ctx **out)
     c->mask = cfg->lora_mask;
     c->n_qkv = 0;
     for (int p = 0; p < 3; ++p) c->qkv_idx[p] = adapted(c, p) ? c->n_qkv++ : -1;
-    c->nz_qkv = c->n_qkv <= 2 ? 32 : 64;
+    c->nz_qkv = 16 * c->n_qkv;
     c->k2_qkv = 16 * c->n_qkv;
+    c->k2p_qkv = (c->k2_qkv + 31) / 32 * 32;
     c->frozen.assign(c->L, {});
     c->adapters.assign(c->L, {});
     c->ws = nullptr; c->ws_bytes = 0;
@@ -450,7 +451,7 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
                     a.zmat[p] = at<bf16>(c, b.fz[p]); a.tmat[p] = at<bf16>(c, b.ft[p]);
                     a.zspill[p] = at<bf16>(c, b.zs[p]);
                 }
-            if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? 16 : 0, st))) return rc;
         }
         if ((rc = launch_attn_fwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<bf16>(c, b.o_lo), at<float>(c, b.lse), c->n_seq,
                                   c->S, c->H,
@@ -465,7 +466,7 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
                 a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_O]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_O]);
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_O]);
             }
-            if ((rc = launch_gemm(a, EPI_RESID, ad ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_RESID, ad ? 16 : 0, st))) return rc;
         }
         bf16 *u2 = at<bf16>(c, b.u2 ? b.u2 : c->t_u2);
         if ((rc = launch_ln_fwd(at<float>(c, b.h_mid), nullptr, nullptr, fz[SLORA_LN2_G], fz[SLORA_LN2_B],
@@ -481,7 +482,7 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
                 a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_FC]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_FC]);
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_FC]);
             }
-            if ((rc = launch_gemm(a, EPI_GELU, ad ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_GELU, ad ? 16 : 0, st))) return rc;
         }
         // h'' = h' + g Wpr^T + bpr (+ adapter): next block's input, or y for the last block
         {
@@ -494,7 +495,7 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
                 a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_PR]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_PR]);
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_PR]);
             }
-            if ((rc = launch_gemm(a, EPI_RESID, ad ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_RESID, ad ? 16 : 0, st))) return rc;
         }
     }
     c->state = 1;
@@ -530,7 +531,7 @@ int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, vo
                 a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_PR]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_PR]);
                 a.zspill[0] = ps;
             }
-            if ((rc = launch_gemm(a, EPI_DGELU, ad ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_DGELU, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_PR, at<bf16>(c, b.g), dff, dh2_16, d, ps, SL_RP, st)))
                 return rc;
         }
@@ -544,7 +545,7 @@ int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, vo
                 a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_FC]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_FC]);
                 a.zspill[0] = ps;
             }
-            if ((rc = launch_gemm(a, EPI_STORE, ad ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_FC, at<bf16>(c, b.u2), d, df, dff, ps, SL_RP, st))) return rc;
         }
         // dh' = dh'' + LN2^T(du2)
@@ -563,7 +564,7 @@ int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, vo
                 a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_O]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_O]);
                 a.zspill[0] = ps;
             }
-            if ((rc = launch_gemm(a, EPI_STORE, ad ? 32 : 0, st))) return rc;
+            if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_O, at<bf16>(c, b.o), d, dh1_16, d, ps, SL_RP, st))) return rc;
         }
         // attention backward
@@ -578,7 +579,7 @@ int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, vo
             a.out0 = dub;
             if (c->n_qkv) {
                 a.zmat[0] = at<bf16>(c, b.bz_qkv); a.tmat[0] = at<bf16>(c, b.bt_qkv); a.zspill[0] = ps;
-                a.K2 = c->k2_qkv; a.ldt = c->k2_qkv;
+                a.K2 = c->k2_qkv; a.ldt = c->k2p_qkv;
             }
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? c->nz_qkv : 0, st))) return rc;
             for (int p = 0; p < 3; ++p)
@@ -654,10 +655,10 @@ LinWs lin_ws(int T, int n_in, int n_out)
     LinWs w;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = al256(off + bytes); return o; };
-    w.A16 = take(2 * 32 * (size_t)n_in);
-    w.B16 = take(2 * (size_t)n_out * 16);
-    w.B16T = take(2 * 32 * (size_t)n_out);
-    w.A16T = take(2 * (size_t)n_in * 16);
+    w.A16 = take(2 * 16 * (size_t)n_in);
+    w.B16 = take(2 * (size_t)n_out * 32);
+    w.B16T = take(2 * 16 * (size_t)n_out);
+    w.A16T = take(2 * (size_t)n_in * 32);
     w.zs = take(2 * (size_t)T * 16);
     w.ps = take(2 * (size_t)T * 16);
     w.WT = take(2 * (size_t)n_in * n_out);
@@ -699,12 +700,12 @@ int slora_lora_linear_fwd(int dtype, int T, int n_in, int n_out, int r, float al
     const LinWs w = lin_ws(T, n_in, n_out);
     char *base = (char *)ws;
     int rc;
-    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 32, n_in, 0, st))) return rc;
-    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16), n_out, 16, 0, st))) return rc;
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 16, n_in, 0, st))) return rc;
+    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16), n_out, 32, 0, st))) return rc;
     GemmArgs a = gemm_base((const bf16 *)x, n_in, (const bf16 *)W, T, n_out, n_in, (const bf16 *)bias, s);
     a.zmat[0] = (bf16 *)(base + w.A16); a.tmat[0] = (bf16 *)(base + w.B16); a.zspill[0] = (bf16 *)(base + w.zs);
     a.out0 = y;
-    return launch_gemm(a, EPI_STORE, 32, st);
+    return launch_gemm(a, EPI_STORE, 16, st);
 }
 
 int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias, void *y,
@@ -739,13 +740,13 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
     if ((rc = slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, x, W, nullptr, A, B, base + w.ytmp, ws, ws_bytes,
                                     stream)))
         return rc;
-    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16T), 32, n_out, 1, st))) return rc;
-    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16T), n_in, 16, 1, st))) return rc;
+    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16T), 16, n_out, 1, st))) return rc;
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16T), n_in, 32, 1, st))) return rc;
     if ((rc = launch_transpose_bf16((const bf16 *)W, n_out, n_in, (bf16 *)(base + w.WT), st))) return rc;
     GemmArgs a = gemm_base((const bf16 *)dy, n_out, (bf16 *)(base + w.WT), T, n_in, n_out, nullptr, s);
     a.zmat[0] = (bf16 *)(base + w.B16T); a.tmat[0] = (bf16 *)(base + w.A16T); a.zspill[0] = (bf16 *)(base + w.ps);
     a.out0 = dx;
-    if ((rc = launch_gemm(a, EPI_STORE, 32, st))) return rc;
+    if ((rc = launch_gemm(a, EPI_STORE, 16, st))) return rc;
     float *part = (float *)(base + w.part);
     if ((rc = launch_lora_grad((const bf16 *)x, n_in, n_in, (bf16 *)(base + w.ps), 16, r, T, part, dA, 1, st)))
         return rc;

@@ -67,10 +67,10 @@ struct GemmArgs {
     int nseg, seg_n;
     const bf16 *bias;                // [N] or null
     // low-rank branch, per segment (null zmat = segment not adapted)
-    const bf16 *zmat[3]; int ldz;    // [NZ,K]: rows of the down-projection, zero rows beyond the rank
-    const bf16 *tmat[3]; int ldt;    // [seg_n,K2]: up-projection, K2 contiguous
+    const bf16 *zmat[3]; int ldz;    // [NZ,K]: rows of the down-projection(s), 16 per adapter, zero beyond the rank
+    const bf16 *tmat[3]; int ldt;    // [seg_n,ldt]: up-projection, ldt = NZ rounded up to 32, zero beyond the rank
     bf16 *zspill[3];                 // [M,K2] or null: scaled bf16 copy of the rank-space activations
-    int K2; float zscale;
+    int K2; float zscale;            // K2 = NZ
     // epilogue
     void *out0; void *out1; const void *aux; int ldo;
 };

@@ -10,8 +10,8 @@
 // MFMA steps; the first column tile of a segment also spills it ([M,K2] bf16) because the
 // adapter-gradient kernels need it.
 //
-// Tiling: 256x256x64 block tile, 8 waves (2 x 4), wave tile 128x64 = 4x2 MFMA 32x32x16
-// tiles; two LDS stages filled by asynchronous global->LDS copies (no staging registers),
+// Tiling: 256x256x64 block tile, 8 waves (2 x 4), wave tile 128x64 = 8x4 MFMA 16x16x32
+// tiles (measured ~8 % faster than 32x32x16 on this power-limited part); two LDS stages filled by asynchronous global->LDS copies (no staging registers),
 // 16-byte XOR-swizzled LDS rows so that both the copies and the MFMA operand reads are
 // bank-conflict free.
 #include "common.h"
@@ -97,10 +97,29 @@ __device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, 
                                      (__attribute__((address_space(3))) void *)(lp), 16, 0, 0)
 #define SL_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)   // vmcnt(0): this wave's copies have landed
 
+// The same copy with a scalar 64-bit base and a 32-bit per-lane byte offset, which keeps the address
+// down to one VGPR per row.  `lds` is the wave-uniform LDS byte address the 1 KB lands at.  Waiting
+// for completion (SL_WAIT_VM0 + barrier) is the caller's job, as with the builtin.
+__device__ __forceinline__ void glds_soff(const void *sbase, unsigned voff, unsigned lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ unsigned lds_addr(const void *p)
+{
+    return (unsigned)(unsigned long long)(const __attribute__((address_space(3))) char *)p;
+}
+
+// NZ = number of rank-space columns handled in the K loop: 16 per adapter whose down-projection
+// spans this K range (0, 16, 32 or 48).  K2P = NZ rounded up to the MFMA k-step of 32.
 template <int EPI, int NZ>
 __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 {
     constexpr int ZB = NZ * ROWB, STAGE = XB + WB + ZB;
+    constexpr int K2P = NZ > 0 ? (NZ + 31) / 32 * 32 : 32;   // (32 keeps array sizes legal when NZ = 0)
+    constexpr int NZT = NZ > 0 ? NZ / 16 : 1;            // 16-column tiles of z
     // two pipeline stages as separate objects, so that reads of one are not ordered behind the
     // asynchronous copies into the other
     __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE];
@@ -109,7 +128,7 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
-    const int r32 = lane & 31, g = lane >> 5;
+    const int r16 = lane & 15, kg = lane >> 4;           // MFMA 16x16x32: row/column r16, k-group kg
 
     // ---- tile of this block; consecutive logical tiles go to the same XCD (blocks are
     //      handed to the 8 XCDs round-robin) so an XCD's L2 sees each X row tile once.
@@ -139,74 +158,86 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
     //      stage, 8 rows (1 KB) per instruction.  Lane l fills 16-byte slot l of the 1 KB chunk:
     //      row l>>3, physical k-chunk l&7, which holds logical k-chunk (l&7) ^ (l>>3) (XOR swizzle).
     const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
-    const bf16 *xp[4], *wp[4];
+    // 32-bit byte offsets from the (scalar) matrix bases keep the address registers few
+    unsigned xo[4], wo[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int row = min(m0 + wave * 32 + p * 8 + lrow, a.M - 1);
         const int n = min(n0 + wave * 32 + p * 8 + lrow, n_end - 1);
-        xp[p] = a.X + (size_t)row * a.ldx + lch * 8;
-        wp[p] = a.W + (size_t)n * a.ldw + lch * 8;
+        xo[p] = ((unsigned)row * (unsigned)a.ldx + lch * 8) * 2u;
+        wo[p] = ((unsigned)n * (unsigned)a.ldw + lch * 8) * 2u;
     }
     const bool zload = (NZ > 0) && has_z && (wave < NZ / 8);
-    const bf16 *zp = zload ? a.zmat[seg] + (size_t)(wave * 8 + lrow) * a.ldz + lch * 8 : nullptr;
+    const unsigned zo = zload ? ((unsigned)(wave * 8 + lrow) * (unsigned)a.ldz + lch * 8) * 2u : 0u;
+    const char *Xb = (const char *)a.X, *Wb = (const char *)a.W;
+    const char *Zb = (NZ > 0 && has_z) ? (const char *)a.zmat[seg] : (const char *)a.X;
     const int wofs = wave * 32 * ROWB;
 
-    f32x16 acc[4][2];
+    // wave tile 128 x 64 = 8 x 4 MFMA 16x16x32 tiles; lane holds column r16, rows 4 kg + e of each
+    f32x4 acc[8][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-    f32x16 zacc[NZ > 0 ? NZ / 32 : 1];
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
+    // rank-space activations of this wave's 32-row slice (rows wm*128 + wn*32 ..): 2 x NZT tiles
+    f32x4 zacc[2][NZT];
 #pragma unroll
-    for (int q = 0; q < (NZ > 0 ? NZ / 32 : 1); ++q)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) zacc[q][e] = 0.0f;
+        for (int q = 0; q < NZT; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) zacc[h][q][e] = 0.0f;
 
-    const int a_row = (wm * 128 + r32) * ROWB;
-    const int b_row = (wn * 64 + r32) * ROWB;
-    const int z_row = (wm * 128 + wn * 32 + r32) * ROWB;
-    const int sw = r32 & 7;
+    const int a_row = (wm * 128 + r16) * ROWB;
+    const int b_row = (wn * 64 + r16) * ROWB;
+    const int z_row = (wm * 128 + wn * 32 + r16) * ROWB;
+    const int sw = r16 & 7;
 
 #define GEMM_ISSUE1(st, k0, p)                                        \
     {                                                                 \
-        SL_GLDS(xp[p] + (k0), (st) + wofs + (p) * 1024);              \
-        SL_GLDS(wp[p] + (k0), (st) + XB + wofs + (p) * 1024);         \
-        if (NZ > 0 && (p) == 0 && zload) SL_GLDS(zp + (k0), (st) + XB + WB + wave * 1024); \
+        glds_soff(Xb + (size_t)(k0) * 2, xo[p], lds_addr(st) + wofs + (p) * 1024);     \
+        glds_soff(Wb + (size_t)(k0) * 2, wo[p], lds_addr(st) + XB + wofs + (p) * 1024); \
+        if (NZ > 0 && (p) == 0 && zload) glds_soff(Zb + (size_t)(k0) * 2, zo, lds_addr(st) + XB + WB + wave * 1024); \
     }
-#define GEMM_STEP(st, ks)                                                                              \
+    // one MFMA k-step of 32: operands in two halves of 4 row tiles to keep the live registers low
+#define GEMM_STEP(st, k2)                                                                              \
     {                                                                                                  \
         const unsigned char *Xs = (st), *Ws = (st) + XB, *Zs = (st) + XB + WB;                         \
-        const int co = (((ks) * 2 + g) ^ sw) << 4;                                                     \
-        bf16x8 af[4], bfr[2];                                                                          \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
-            af[i] = *(const bf16x8 *)(Xs + a_row + i * 32 * ROWB + co);                                \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
-            bfr[j] = *(const bf16x8 *)(Ws + b_row + j * 32 * ROWB + co);                               \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
-            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+        const int co = (((k2) * 4 + kg) ^ sw) << 4;                                                    \
+        bf16x8 bfr[4];                                                                                 \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                  \
+            bfr[j] = *(const bf16x8 *)(Ws + b_row + j * 16 * ROWB + co);                               \
+        _Pragma("unroll") for (int ih = 0; ih < 2; ++ih) {                                             \
+            bf16x8 af[4];                                                                              \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
+                af[i] = *(const bf16x8 *)(Xs + a_row + (ih * 4 + i) * 16 * ROWB + co);                 \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                          \
+                    acc[ih * 4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                      \
+                        af[i], bfr[j], acc[ih * 4 + i][j], 0, 0, 0);                                   \
+            if (NZ > 0) __builtin_amdgcn_sched_barrier(0);                                             \
+        }                                                                                              \
         if (NZ > 0 && has_z) {                                                                         \
-            bf16x8 za = *(const bf16x8 *)(Xs + z_row + co);                                            \
-            _Pragma("unroll") for (int q = 0; q < NZ / 32; ++q) {                                      \
-                bf16x8 zb = *(const bf16x8 *)(Zs + (q * 32 + r32) * ROWB + co);                        \
-                zacc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, zb, zacc[q], 0, 0, 0);           \
+            bf16x8 za[2];                                                                              \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h)                                              \
+                za[h] = *(const bf16x8 *)(Xs + z_row + h * 16 * ROWB + co);                            \
+            _Pragma("unroll") for (int q = 0; q < NZT; ++q) {                                          \
+                const bf16x8 zb = *(const bf16x8 *)(Zs + (q * 16 + r16) * ROWB + co);                  \
+                _Pragma("unroll") for (int h = 0; h < 2; ++h)                                          \
+                    zacc[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(za[h], zb, zacc[h][q], 0, 0, 0); \
             }                                                                                          \
         }                                                                                              \
     }
-    // one k-slab of 64: the copies for the next slab are issued a quarter at a time between the
-    // four MFMA groups so that no wave sits in the memory-issue queue while its MFMAs wait
+    // one k-slab of 64: the copies for the next slab are issued half at a time before the two MFMA
+    // groups so that no wave sits in the memory-issue queue while its MFMAs wait
 #define GEMM_PHASE(cur, nxt, k0, doload)                              \
     {                                                                 \
-        if (doload) GEMM_ISSUE1(nxt, k0, 0)                           \
+        if (doload) { GEMM_ISSUE1(nxt, k0, 0) GEMM_ISSUE1(nxt, k0, 1) } \
         GEMM_STEP(cur, 0) __builtin_amdgcn_sched_barrier(0);          \
-        if (doload) GEMM_ISSUE1(nxt, k0, 1)                           \
+        if (doload) { GEMM_ISSUE1(nxt, k0, 2) GEMM_ISSUE1(nxt, k0, 3) } \
         GEMM_STEP(cur, 1) __builtin_amdgcn_sched_barrier(0);          \
-        if (doload) GEMM_ISSUE1(nxt, k0, 2)                           \
-        GEMM_STEP(cur, 2) __builtin_amdgcn_sched_barrier(0);          \
-        if (doload) GEMM_ISSUE1(nxt, k0, 3)                           \
-        GEMM_STEP(cur, 3) __builtin_amdgcn_sched_barrier(0);          \
     }
 
     const int nk = a.K / BK;
@@ -230,30 +261,31 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 #undef GEMM_ISSUE1
 #undef GEMM_STEP
 #undef GEMM_PHASE
-    unsigned char *smem = st0;
 
-    // ---- low-rank tail: acc += (zscale * z)[256,K2] . T[n,K2]^T -----------------------------
+    // ---- low-rank tail: acc += (zscale * z)[256,K2P] . T[n,K2P]^T -----------------------------
     if (NZ > 0 && has_z) {
-        constexpr int ZP = NZ + 8;                       // LDS pitch of the z tile, in elements
-        bf16 *zs = (bf16 *)smem;                         // the K loop is over: reuse stage 0
+        constexpr int ZP = K2P + 8;                      // LDS pitch of the z tile, in elements
+        bf16 *zs = (bf16 *)st0;                          // the K loop is over: reuse stage 0
         const bf16 *tm_ = a.tmat[seg];
-        const int nks = a.K2 >> 4;
-        // issue the up-projection operand loads early (L2 hits; at most 4 k-steps of 16)
-        bf16x8 tb[4][2];
+        // up-projection operands (L2 hits): column n0 + wn*64 + j*16 + r16, k = ks*32 + kg*8 ..
+        bf16x8 tb[K2P / 32][4];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
+        for (int ks = 0; ks < K2P / 32; ++ks)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int n = min(n0 + wn * 64 + j * 32 + r32, n_end - 1) - seg * a.seg_n;
-                if (ks < nks) tb[ks][j] = *(const bf16x8 *)(tm_ + (size_t)n * a.ldt + ks * 16 + g * 8);
+            for (int j = 0; j < 4; ++j) {
+                const int n = min(n0 + wn * 64 + j * 16 + r16, n_end - 1) - seg * a.seg_n;
+                tb[ks][j] = *(const bf16x8 *)(tm_ + (size_t)n * a.ldt + ks * 32 + kg * 8);
             }
+        // scaled, rounded z of this wave's 32 rows; columns NZ..K2P of the tile are zero
 #pragma unroll
-        for (int q = 0; q < NZ / 32; ++q)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int row = wm * 128 + wn * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                zs[row * ZP + q * 32 + r32] = f2bf(zacc[q][e] * a.zscale);
-            }
+            for (int q = 0; q < K2P / 16; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int row = wm * 128 + wn * 32 + h * 16 + 4 * kg + e;
+                    zs[row * ZP + q * 16 + r16] = f2bf(q < NZT ? zacc[h][q < NZT ? q : 0][e] * a.zscale : 0.f);
+                }
         __syncthreads();
         if (a.zspill[seg] != nullptr && tns == 0) {
             const int cpr = a.K2 >> 3;                   // 16-byte chunks per row
@@ -265,26 +297,28 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
             }
         }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < nks) {
+        for (int ks = 0; ks < K2P / 32; ++ks) {
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih) {
                 bf16x8 af[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    af[i] = *(const bf16x8 *)(zs + (wm * 128 + i * 32 + r32) * ZP + ks * 16 + g * 8);
+                    af[i] = *(const bf16x8 *)(zs + (wm * 128 + (ih * 4 + i) * 16 + r16) * ZP + ks * 32 + kg * 8);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], tb[ks][j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < 4; ++j)
+                        acc[ih * 4 + i][j] =
+                            __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], tb[ks][j], acc[ih * 4 + i][j], 0, 0, 0);
             }
         }
     }
 
-    // ---- epilogue.  A lane holds column (lane & 31) of each 32x32 tile, rows 8(e/4) + 4g + e%4:
-    //      each wave transposes its tiles through a private LDS strip (32 rows x 64 columns fp32)
-    //      so that global memory sees 16-byte accesses, 8 rows x 128..256 contiguous bytes per
-    //      instruction.  Only the owning wave touches its strip, so no block barrier is needed.
-    constexpr int EP = 72;                               // strip pitch in floats (bank-conflict free)
+    // ---- epilogue.  A lane holds column r16 of each 16x16 tile, rows 4 kg + e: each wave transposes
+    //      its tiles through a private LDS strip (32 rows x 64 columns fp32) so that global memory
+    //      sees 16-byte accesses, 8 rows x 128..256 contiguous bytes per instruction.  Only the
+    //      owning wave touches its strip, so no block barrier is needed.
+    constexpr int EP = 68;                               // strip pitch in floats (bank-conflict free)
     if (NZ > 0 && has_z) __syncthreads();                // the z tile in st0 has been consumed
     float *stg = (float *)((wave < 4 ? st0 : st1) + (wave & 3) * (32 * EP * 4));
     const int er = lane >> 3, ec = (lane & 7) * 8;
@@ -306,7 +340,7 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
         load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[0][it]);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {                        // strip i = rows 32 i .. 32 i + 31 of the wave tile
         if (i + 1 < 4) {
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
@@ -315,10 +349,12 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
             }
         }
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stg[(8 * (e >> 2) + 4 * g + (e & 3)) * EP + j * 32 + r32] = acc[i][j][e];
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    stg[(h * 16 + 4 * kg + e) * EP + j * 16 + r16] = acc[2 * i + h][j][e];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int rl = it * 8 + er;
@@ -349,8 +385,9 @@ int launch_e(const GemmArgs &a, int nz, hipStream_t st)
 {
     switch (nz) {
     case 0: return launch_t<EPI, 0>(a, st);
+    case 16: return launch_t<EPI, 16>(a, st);
     case 32: return launch_t<EPI, 32>(a, st);
-    case 64: return launch_t<EPI, 64>(a, st);
+    case 48: return launch_t<EPI, 48>(a, st);
     }
     return -1;
 }
@@ -418,7 +455,7 @@ static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
     if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K % BK) != 0 || a.nseg < 1 || a.nseg > 3 ||
         a.nseg * a.seg_n != a.N || (a.ldx % 8) || (a.ldw % 8) || (a.seg_n % 8) || (a.ldo % 8))
         return -1;
-    if (nz > 0 && (a.K2 < 16 || a.K2 > nz || (a.K2 % 16) || (a.ldt % 8) || (a.ldz % 8))) return -1;
+    if (nz > 0 && (a.K2 != nz || (a.ldt % 8) || a.ldt < (nz + 31) / 32 * 32 || (a.ldz % 8))) return -1;
     switch (epi) {
     case EPI_STORE: return launch_e<EPI_STORE>(a, nz, st);
     case EPI_RESID: return launch_e<EPI_RESID>(a, nz, st);
