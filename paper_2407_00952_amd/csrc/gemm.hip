@@ -11,9 +11,9 @@
 // adapter-gradient kernels need it.
 //
 // Tiling: 256x256x64 block tile, 8 waves (2 x 4), wave tile 128x64 = 8x4 MFMA 16x16x32
-// tiles (measured ~8 % faster than 32x32x16 on this power-limited part); two LDS stages filled by asynchronous global->LDS copies (no staging registers),
-// 16-byte XOR-swizzled LDS rows so that both the copies and the MFMA operand reads are
-// bank-conflict free.
+// tiles (measured ~8 % faster than 32x32x16 on this power-limited part); two LDS stages filled
+// by asynchronous global->LDS copies (no staging registers), 16-byte XOR-swizzled LDS rows
+// so that both the copies and the MFMA operand reads are bank-conflict free.
 #include "common.h"
 #include <vector>
 
@@ -102,10 +102,12 @@ __device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, 
 // for completion (SL_WAIT_VM0 + barrier) is the caller's job, as with the builtin.
 __device__ __forceinline__ void glds_soff(const void *sbase, unsigned voff, unsigned lds)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+    // M0 carries the LDS address; one wait state is required between its write and the copy.
+    // Nothing else in these kernels uses M0, so it is not listed as clobbered.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
+                 : "memory");
 }
 __device__ __forceinline__ unsigned lds_addr(const void *p)
 {
