@@ -195,3 +195,31 @@ def make_fedavg_inputs(n_clients=16, n_params=None, seed=BASE_SEED + 5 + 1000, c
         vecs = [_normal(rng, (n_params,), 0.02) for _ in range(n_clients)]
     counts = rng.integers(100, 1001, size=n_clients).astype(np.int64)
     return vecs, counts
+
+
+GPT2_VOCAB = 50257
+
+
+def make_loss_head_inputs(n_seq, seq_len, d_model, vocab=GPT2_VOCAB, seed=BASE_SEED + 3 + 2000, quant=True,
+                          y_std=1.0):
+    """Inputs of the server's loss head: final LayerNorm, vocabulary matrix, stack output, labels.
+
+    Returns dict(lnf_g [d], lnf_b [d], Wv [V,d], y [n_seq*S, d], labels [n_seq*S] int32).
+    Labels follow the shape of prompt-completion fine-tuning data: in every sequence a context of
+    c ~ U[S/4, S/2) leading tokens carries no label (-1), the rest are uniform over the vocabulary.
+    Draw order: lnf_g, lnf_b, Wv, y, then per sequence c and its labels.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = round_bf16 if quant else (lambda a: a)
+    out = {}
+    out["lnf_g"] = q(_normal(rng, (d_model,), 0.02, 1.0))
+    out["lnf_b"] = q(_normal(rng, (d_model,), 0.02))
+    out["Wv"] = q(_normal(rng, (vocab, d_model), 0.02))
+    out["y"] = q(_normal(rng, (n_seq * seq_len, d_model), y_std))
+    labels = np.empty((n_seq, seq_len), dtype=np.int32)
+    for s in range(n_seq):
+        c = int(rng.integers(max(seq_len // 4, 0), max(seq_len // 2, 1)))
+        labels[s] = rng.integers(0, vocab, size=seq_len).astype(np.int32)
+        labels[s, :c] = -1
+    out["labels"] = labels.reshape(-1)
+    return out
