@@ -132,6 +132,29 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
 int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias,
                              void *y, void *stream);
 
+/* ---- loss head of the server (Sec. III-B: labels arrive with the activations in step a2; step a3
+ *      computes the loss from the predicted value and the labels and derives the gradients from it) --- */
+/* GPT-2's head on the stack output y [T, d_model] (bf16): u = LayerNorm(y; lnf_g, lnf_b, eps),
+ * logits = u Wv^T against the frozen token-embedding matrix Wv [vocab, d_model] (bf16, no bias),
+ *   loss_tok[t] = logsumexp_v logits[t, v] - logits[t, labels[t]]      (0 where the token has no label)
+ *   loss        = sum_t loss_tok[t] / n,  n = number of labeled tokens   (device float)
+ *   dy [T, d_model] (bf16) = d loss / d y   -- the dy argument of slora_server_bwd.
+ * labels [T] int32 on the device; a label outside 0..vocab-1 marks a token without label (context
+ * tokens).  With no labeled token at all, loss is NaN and dy is all zeros.  Logits are rounded to bf16
+ * before the softmax, probabilities are evaluated in fp32.  Nothing in the head is trainable.
+ * d_model a multiple of 64, <= 2048; vocab <= 65536.  All pointers device pointers, 16-byte aligned;
+ * ws 256-byte aligned, caller-owned, slora_loss_head_ws_bytes(max_tokens, ...) bytes; its first part
+ * holds a zero-padded and a transposed copy of Wv written by slora_loss_head_prepare (call it once, and
+ * again only if Wv changes); the rest is scratch.  T <= max_tokens.  Nothing synchronises the stream.
+ * Returns SLORA_EINVAL / SLORA_ENOSPC / SLORA_EHIP like the other calls (0 bytes from _ws_bytes on
+ * invalid sizes). */
+size_t slora_loss_head_ws_bytes(int32_t max_tokens, int32_t d_model, int32_t vocab);
+int slora_loss_head_prepare(int32_t d_model, int32_t vocab, const void *Wv, void *ws, size_t ws_bytes,
+                            void *stream);
+int slora_loss_head(int32_t T, int32_t d_model, int32_t vocab, const void *y, const void *lnf_g,
+                    const void *lnf_b, float eps, const int32_t *labels, void *ws, size_t ws_bytes,
+                    float *loss_tok, float *loss, void *dy, void *stream);
+
 /* ---- measurement hook (not part of the method) ---------------------------------------------------- */
 /* While enabled, every launch of the bf16 GEMM kernel (the frozen products of Sec. II-C with the
  * fused low-rank branch) is bracketed by HIP events on its stream.  slora_prof_read waits for the

@@ -26,7 +26,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_bind_frozen", "slora_bind_adapter", "slora_server_fwd", "slora_server_bwd",
            "slora_adapter_step", "slora_fedavg", "slora_lora_linear_ws_bytes", "slora_lora_linear_fwd",
            "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error", "slora_prof_enable",
-           "slora_prof_read", "slora_frozen_linear_bf16"]
+           "slora_prof_read", "slora_frozen_linear_bf16", "slora_loss_head_ws_bytes",
+           "slora_loss_head_prepare", "slora_loss_head"]
 
 
 class slora_config(ctypes.Structure):
@@ -69,6 +70,10 @@ def lib():
         L.slora_lora_linear_fwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_lora_linear_bwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_frozen_linear_bf16.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
+        L.slora_loss_head_ws_bytes.argtypes = [i32, i32, i32]
+        L.slora_loss_head_ws_bytes.restype = sz
+        L.slora_loss_head_prepare.argtypes = [i32, i32, vp, vp, sz, vp]
+        L.slora_loss_head.argtypes = [i32, i32, i32, vp, vp, vp, f32, vp, vp, sz, vp, vp, vp, vp]
         L.slora_prof_enable.argtypes = [i32]
         L.slora_prof_read.argtypes = [vp, vp, vp]
         L.slora_strerror.argtypes = [i32]
@@ -174,6 +179,19 @@ def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, d
 
 def slora_frozen_linear_bf16(T, n_in, n_out, x, W, bias, y, stream=None):
     _check(lib().slora_frozen_linear_bf16(T, n_in, n_out, _p(x), _p(W), _p(bias), _p(y), _stream(stream)))
+
+
+def slora_loss_head_ws_bytes(max_tokens, d_model, vocab):
+    return int(lib().slora_loss_head_ws_bytes(max_tokens, d_model, vocab))
+
+
+def slora_loss_head_prepare(d_model, vocab, Wv, ws, ws_bytes, stream=None):
+    _check(lib().slora_loss_head_prepare(d_model, vocab, _p(Wv), _p(ws), ws_bytes, _stream(stream)))
+
+
+def slora_loss_head(T, d_model, vocab, y, lnf_g, lnf_b, eps, labels, ws, ws_bytes, loss_tok, loss, dy, stream=None):
+    _check(lib().slora_loss_head(T, d_model, vocab, _p(y), _p(lnf_g), _p(lnf_b), eps, _p(labels), _p(ws), ws_bytes,
+                                 _p(loss_tok), _p(loss), _p(dy), _stream(stream)))
 
 
 def slora_prof_enable(on):

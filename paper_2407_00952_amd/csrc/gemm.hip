@@ -457,6 +457,9 @@ static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
     if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K % BK) != 0 || a.nseg < 1 || a.nseg > 3 ||
         a.nseg * a.seg_n != a.N || (a.ldx % 8) || (a.ldw % 8) || (a.seg_n % 8) || (a.ldo % 8))
         return -1;
+    // the copies address both operands with 32-bit byte offsets from their bases
+    if ((unsigned long long)a.M * a.ldx * 2ull >= (1ull << 32) || (unsigned long long)a.N * a.ldw * 2ull >= (1ull << 32))
+        return -1;
     if (nz > 0 && (a.K2 != nz || (a.ldt % 8) || a.ldt < (nz + 31) / 32 * 32 || (a.ldz % 8))) return -1;
     switch (epi) {
     case EPI_STORE: return launch_e<EPI_STORE>(a, nz, st);

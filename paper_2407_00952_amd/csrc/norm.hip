@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
     if (lane == 0) { stats[2 * row] = mu; stats[2 * row + 1] = rho; }
 }
 
-// DRES16: the residual gradient arrives as bf16 (last block: the caller's dY) instead of fp32.
+// DRES16: the residual gradient arrives as bf16 (last block: the caller's dY) instead of fp32;
+// with DRES16 false a null `dres` means there is no residual gradient to add.
 // SCATTER: the bf16 output goes to the K client buffers.
 template <bool DRES16, bool SCATTER>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du, const float *__restrict__ h,
@@ -131,9 +132,11 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du
                 bf16x4 t = *(const bf16x4 *)((const bf16 *)dres + (size_t)row * d + col);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) r[i] = bf2f(t[i]);
-            } else {
+            } else if (dres != nullptr) {
                 float4 t = *(const float4 *)((const float *)dres + (size_t)row * d + col);
                 r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
+            } else {                                     // no residual branch (the final LayerNorm)
+                r[0] = r[1] = r[2] = r[3] = 0.f;
             }
             bf16x4 o16;
 #pragma unroll

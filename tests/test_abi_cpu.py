@@ -135,6 +135,27 @@ def test_linear_argument_checks():
     assert e.value.code == B.SLORA_EINVAL
 
 
+def test_loss_head_argument_checks():
+    n = B.slora_loss_head_ws_bytes(32768, 1024, 50257)
+    # two copies of the padded vocabulary matrix + one 16384-token chunk of bf16 logits + per-token buffers
+    assert n >= 2 * 2 * 50304 * 1024 + 2 * 16384 * 50304 + 32768 * 1024 * (2 + 4 + 2)
+    assert B.slora_loss_head_ws_bytes(32768, 1000, 50257) == 0       # d_model not a multiple of 64
+    assert B.slora_loss_head_ws_bytes(32768, 1024, 70000) == 0       # vocabulary too large
+    assert B.slora_loss_head_ws_bytes(0, 1024, 50257) == 0
+    with pytest.raises(B.SloraError) as e:
+        B.slora_loss_head_prepare(1024, 50257, None, FAKE, n, stream=0)
+    assert e.value.code == B.SLORA_EINVAL
+    with pytest.raises(B.SloraError) as e:
+        B.slora_loss_head_prepare(1024, 50257, FAKE, FAKE, 1024, stream=0)
+    assert e.value.code == B.SLORA_ENOSPC
+    with pytest.raises(B.SloraError) as e:
+        B.slora_loss_head(128, 1024, 50257, FAKE, FAKE, FAKE, 1e-5, None, FAKE, n, FAKE, FAKE, FAKE, stream=0)
+    assert e.value.code == B.SLORA_EINVAL
+    with pytest.raises(B.SloraError) as e:
+        B.slora_loss_head(128, 1024, 50257, FAKE, FAKE, FAKE, 1e-5, FAKE, FAKE, 4096, FAKE, FAKE, FAKE, stream=0)
+    assert e.value.code == B.SLORA_ENOSPC
+
+
 def test_strerror():
     L = B.lib()
     assert L.slora_strerror(0) == b"ok"
