@@ -79,6 +79,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=3, help="2..5 (3 = GPT-2-medium split, the metric's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--loss-head", action="store_true",
+                    help="put the loss head (final LayerNorm, vocabulary logits, cross-entropy -> dY) between "
+                         "forward and backward inside the timed step; without it the step takes dY as given and "
+                         "the loss head is timed on its own after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps, run a plain copy of known size (FedAvg with one client, "
                          "256 MiB in, 256 MiB out) so that HBM byte counters can be scaled")
@@ -107,10 +111,31 @@ def main():
     fed_out = torch.empty(n_fed, dtype=torch.float32, device="cuda")
     lr = 2e-4
     stream = torch.cuda.current_stream().cuda_stream
+    # loss head: GPT-2's vocabulary, labels with a context part that carries no label
+    V = synth.GPT2_VOCAB
+    lh = synth.make_loss_head_inputs(cfg.n_seq, cfg.seq_len, cfg.d_model, vocab=V)
+    lh_bytes = B.slora_loss_head_ws_bytes(cfg.tokens, cfg.d_model, V)
+    lh_ws = torch.empty(lh_bytes, dtype=torch.uint8, device="cuda")
+    lh_Wv = B.to_device_bf16(lh["Wv"])
+    B.slora_loss_head_prepare(cfg.d_model, V, lh_Wv, lh_ws, lh_bytes, stream)
+    lh_g, lh_b = B.to_device_bf16(lh["lnf_g"]), B.to_device_bf16(lh["lnf_b"])
+    lh_labels = torch.from_numpy(lh["labels"]).cuda()
+    lh_tok = torch.empty(cfg.tokens, dtype=torch.float32, device="cuda")
+    lh_loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    lh_dy = torch.empty_like(dy)
+    del lh
+
+    def loss_head():
+        B.slora_loss_head(cfg.tokens, cfg.d_model, V, y, lh_g, lh_b, cfg.ln_eps, lh_labels, lh_ws, lh_bytes, lh_tok,
+                          lh_loss, lh_dy, stream)
 
     def step():
         srv.fwd(xs, y, stream)
-        srv.bwd(dy, dxs, stream)
+        if args.loss_head:
+            loss_head()
+            srv.bwd(lh_dy, dxs, stream)
+        else:
+            srv.bwd(dy, dxs, stream)
         srv.step(lr, stream)
         B.slora_fedavg(fed_dev, fed_counts, n_fed, fed_out, stream)
 
@@ -125,6 +150,17 @@ def main():
     el = time.perf_counter() - t0
     gemm_ms, gemm_flop, launches = B.slora_prof_read()
     B.slora_prof_enable(0)
+
+    # the loss head on its own (outside the timed region and outside the GEMM statistics above)
+    for _ in range(2):
+        loss_head()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(5):
+        loss_head()
+    torch.cuda.synchronize()
+    lh_ms = (time.perf_counter() - t1) / 5 * 1e3
+    lh_flop = 4.0 * cfg.tokens * cfg.d_model * V
 
     if args.copy_calibration:
         n_cal = 64 * 1024 * 1024
@@ -145,10 +181,11 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d server blocks, d=%d, H=%d, d_ff=%d, LoRA r=%d on %s, K=%d clients x %d x %d "
-                               "tokens (T=%d), bf16 activations; step = fwd + bwd + SGD adapter step + FedAvg of "
+                               "tokens (T=%d), bf16 activations; step = fwd + %sbwd + SGD adapter step + FedAvg of "
                                "the K client adapter sets" % (cfg.name, cfg.n_blocks, cfg.d_model, cfg.n_head,
                                                              cfg.d_ff, cfg.lora_r, ",".join(cfg.lora_proj),
-                                                             cfg.n_clients, cfg.batch, cfg.seq_len, cfg.tokens),
+                                                             cfg.n_clients, cfg.batch, cfg.seq_len, cfg.tokens,
+                                                             "loss head (V=%d) + " % V if args.loss_head else ""),
                    "tokens_per_step": cfg.tokens},
         "model_tflops": model_tflops, "model_frac_of_bf16_peak": model_tflops / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (bf16 MFMA GEMM + fused LoRA branch, all shapes)",
@@ -157,6 +194,8 @@ def main():
                      "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
                      "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
     }
+    out["loss_head"] = {"ms": lh_ms, "vocab": V, "tflops": lh_flop / (lh_ms * 1e-3) / 1e12,
+                        "in_timed_step": bool(args.loss_head)}
     if not args.no_cpu_baseline:
         del srv
         torch.cuda.empty_cache()
