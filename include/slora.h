@@ -132,6 +132,25 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
 int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias,
                              void *y, void *stream);
 
+/* ---- client-side model (Sec. III-B a1, Eq. 2: client forward up to the cut layer; a5, Eq. 6-7:
+ *      client backward from the returned activation gradients and SGD on the client adapters) ---------- */
+/* A client's share of the model is a context of its own (slora_create with n_blocks = the number of
+ * client-side blocks; frozen weights and adapters bound as for the server).  The input of its first block
+ * is the embedding of the batch: row t = wte[tokens[t]] + wpe[t mod seq_len], summed in fp32 from the two
+ * frozen bf16 tables (wte [vocab, d_model], wpe [>= seq_len, d_model]); token ids outside 0..vocab-1 are
+ * clamped.  tokens: device int32 [batch * seq_len].  act [batch, seq_len, d_model] bf16 receives the
+ * cut-layer activations that go to the server.  batch <= max_seqs. */
+int slora_client_fwd(slora_ctx *ctx, int32_t batch, const int32_t *tokens, int32_t vocab, const void *wte,
+                     const void *wpe, void *act, void *stream);
+/* dact [batch, seq_len, d_model] bf16 = the activation gradient received from the server (step a4).
+ * Overwrites dA, dB of every bound adapter; no gradient is produced for the embedding (frozen).
+ * Same call order as the server: fwd -> bwd -> slora_adapter_step (Eq. 6-7 with the client rate). */
+int slora_client_bwd(slora_ctx *ctx, const void *dact, void *stream);
+/* Tell a context that the caller has overwritten its bound A / B buffers (the aggregated adapters
+ * coming back in step b3): the bf16 operand copies are rebuilt at the next forward.  Not allowed
+ * between a forward and its backward (SLORA_ESTATE). */
+int slora_adapters_changed(slora_ctx *ctx);
+
 /* ---- loss head of the server (Sec. III-B: labels arrive with the activations in step a2; step a3
  *      computes the loss from the predicted value and the labels and derives the gradients from it) --- */
 /* GPT-2's head on the stack output y [T, d_model] (bf16): u = LayerNorm(y; lnf_g, lnf_b, eps),

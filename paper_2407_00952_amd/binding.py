@@ -27,7 +27,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_adapter_step", "slora_fedavg", "slora_lora_linear_ws_bytes", "slora_lora_linear_fwd",
            "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error", "slora_prof_enable",
            "slora_prof_read", "slora_frozen_linear_bf16", "slora_loss_head_ws_bytes",
-           "slora_loss_head_prepare", "slora_loss_head"]
+           "slora_loss_head_prepare", "slora_loss_head", "slora_client_fwd", "slora_client_bwd",
+           "slora_adapters_changed"]
 
 
 class slora_config(ctypes.Structure):
@@ -70,6 +71,9 @@ def lib():
         L.slora_lora_linear_fwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_lora_linear_bwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_frozen_linear_bf16.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
+        L.slora_client_fwd.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
+        L.slora_client_bwd.argtypes = [vp, vp, vp]
+        L.slora_adapters_changed.argtypes = [vp]
         L.slora_loss_head_ws_bytes.argtypes = [i32, i32, i32]
         L.slora_loss_head_ws_bytes.restype = sz
         L.slora_loss_head_prepare.argtypes = [i32, i32, vp, vp, sz, vp]
@@ -179,6 +183,18 @@ def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, d
 
 def slora_frozen_linear_bf16(T, n_in, n_out, x, W, bias, y, stream=None):
     _check(lib().slora_frozen_linear_bf16(T, n_in, n_out, _p(x), _p(W), _p(bias), _p(y), _stream(stream)))
+
+
+def slora_client_fwd(ctx, batch, tokens, vocab, wte, wpe, act, stream=None):
+    _check(lib().slora_client_fwd(ctx, batch, _p(tokens), vocab, _p(wte), _p(wpe), _p(act), _stream(stream)))
+
+
+def slora_client_bwd(ctx, dact, stream=None):
+    _check(lib().slora_client_bwd(ctx, _p(dact), _stream(stream)))
+
+
+def slora_adapters_changed(ctx):
+    _check(lib().slora_adapters_changed(ctx))
 
 
 def slora_loss_head_ws_bytes(max_tokens, d_model, vocab):

@@ -399,37 +399,15 @@ int slora_bind_adapter(slora_ctx *ctx, int block, int proj, float *A, float *B, 
     return SLORA_OK;
 }
 
-int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const int32_t *h_batch, void *y,
-                     void *stream)
+// Forward through the blocks of a context.  The input of block 0 is either the concatenation of the
+// client buffers in `tab` (server side) or the embedding lookup `emb` (client side).
+static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb, void *y, hipStream_t st)
 {
-    if (!c || !h_x_clients || !h_batch || !y) return SLORA_EINVAL;
-    if (K <= 0 || K > SLORA_MAX_CLIENTS) return SLORA_EINVAL;
-    long long nseq = 0;
-    for (int i = 0; i < K; ++i) {
-        if (!h_x_clients[i] || h_batch[i] <= 0) return SLORA_EINVAL;
-        if (((uintptr_t)h_x_clients[i]) & 7) return SLORA_EINVAL;
-        nseq += h_batch[i];
-    }
-    if (nseq > c->cfg.max_seqs) return SLORA_EINVAL;
-    if (((uintptr_t)y) & 7) return SLORA_EINVAL;
     int rc;
-    if ((rc = check_bound(c))) return rc;
-    hipStream_t st = (hipStream_t)stream;
-
     if (!c->prepared && (rc = prepare(c, st))) return rc;
     if (c->shadows_dirty) {
         if ((rc = refresh_shadows(c, st))) return rc;
         c->shadows_dirty = false;
-    }
-    c->K = K; c->n_seq = (int)nseq; c->T = c->n_seq * c->S;
-    ClientTable tab;
-    tab.K = K;
-    int rows = 0;
-    for (int i = 0; i < K; ++i) {
-        rows += h_batch[i] * c->S;
-        tab.ptr[i] = (void *)h_x_clients[i];
-        tab.row_end[i] = rows;
-        c->row_end[i] = rows;
     }
     c->state = 0;
     const int T = c->T, d = c->d, dff = c->dff;
@@ -438,9 +416,10 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
         const auto &fz = c->frozen[l];
         float *h_in = at<float>(c, b.h_in);
         bf16 *u = at<bf16>(c, b.u ? b.u : c->t_u);
-        // LN1 (block 0 gathers the clients' activations: S = [s_1; ...; s_N])
-        if ((rc = launch_ln_fwd(l == 0 ? nullptr : h_in, l == 0 ? &tab : nullptr, h_in, fz[SLORA_LN1_G],
-                                fz[SLORA_LN1_B], c->cfg.ln_eps, u, at<float>(c, b.stats1), T, d, st)))
+        // LN1 (block 0 gathers the clients' activations: S = [s_1; ...; s_N], or looks the embedding up)
+        if ((rc = launch_ln_fwd(l == 0 ? nullptr : h_in, l == 0 ? tabp : nullptr, h_in, fz[SLORA_LN1_G],
+                                fz[SLORA_LN1_B], c->cfg.ln_eps, u, at<float>(c, b.stats1), T, d, st,
+                                l == 0 ? emb : nullptr)))
             return rc;
         // q | k | v = u Wqkv^T + b (+ adapters)
         {
@@ -502,17 +481,52 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
     return SLORA_OK;
 }
 
-int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, void *stream)
+int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const int32_t *h_batch, void *y,
+                     void *stream)
 {
-    if (!c || !dy || !h_dx_clients) return SLORA_EINVAL;
-    if (c->state != 1) return SLORA_ESTATE;
-    for (int i = 0; i < c->K; ++i)
-        if (!h_dx_clients[i] || (((uintptr_t)h_dx_clients[i]) & 7)) return SLORA_EINVAL;
-    if (((uintptr_t)dy) & 15) return SLORA_EINVAL;
-    hipStream_t st = (hipStream_t)stream;
+    if (!c || !h_x_clients || !h_batch || !y) return SLORA_EINVAL;
+    if (K <= 0 || K > SLORA_MAX_CLIENTS) return SLORA_EINVAL;
+    long long nseq = 0;
+    for (int i = 0; i < K; ++i) {
+        if (!h_x_clients[i] || h_batch[i] <= 0) return SLORA_EINVAL;
+        if (((uintptr_t)h_x_clients[i]) & 7) return SLORA_EINVAL;
+        nseq += h_batch[i];
+    }
+    if (nseq > c->cfg.max_seqs) return SLORA_EINVAL;
+    if (((uintptr_t)y) & 7) return SLORA_EINVAL;
+    int rc;
+    if ((rc = check_bound(c))) return rc;
+    c->K = K; c->n_seq = (int)nseq; c->T = c->n_seq * c->S;
     ClientTable tab;
-    tab.K = c->K;
-    for (int i = 0; i < c->K; ++i) { tab.ptr[i] = h_dx_clients[i]; tab.row_end[i] = c->row_end[i]; }
+    tab.K = K;
+    int rows = 0;
+    for (int i = 0; i < K; ++i) {
+        rows += h_batch[i] * c->S;
+        tab.ptr[i] = (void *)h_x_clients[i];
+        tab.row_end[i] = rows;
+        c->row_end[i] = rows;
+    }
+    return stack_fwd(c, &tab, nullptr, y, (hipStream_t)stream);
+}
+
+int slora_client_fwd(slora_ctx *c, int32_t batch, const int32_t *tokens, int32_t vocab, const void *wte,
+                     const void *wpe, void *act, void *stream)
+{
+    if (!c || !tokens || !wte || !wpe || !act) return SLORA_EINVAL;
+    if (batch <= 0 || batch > c->cfg.max_seqs || vocab <= 0) return SLORA_EINVAL;
+    if ((((uintptr_t)wte) | ((uintptr_t)wpe) | ((uintptr_t)act)) & 7) return SLORA_EINVAL;
+    int rc;
+    if ((rc = check_bound(c))) return rc;
+    c->K = 1; c->n_seq = batch; c->T = batch * c->S;
+    c->row_end[0] = c->T;
+    EmbedSrc emb = {tokens, (const bf16 *)wte, (const bf16 *)wpe, c->S, vocab};
+    return stack_fwd(c, nullptr, &emb, act, (hipStream_t)stream);
+}
+
+// Backward through the blocks of a context.  `tabp` = where the activation gradients of block 0's input
+// go (server side: the clients' buffers); null = nobody needs them (client side: the embedding is frozen).
+static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipStream_t st)
+{
     const int T = c->T, d = c->d, dff = c->dff;
     int rc;
     // gradient of the residual stream entering the block from above: fp32 (+ bf16 GEMM operand)
@@ -597,13 +611,43 @@ int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, vo
                 return rc;
             dh2_32 = nx32;
             dh2_16 = nx16;
-        } else {
+        } else if (tabp) {
             if ((rc = launch_ln_bwd(dub, at<float>(c, b.h_in), at<float>(c, b.stats1), fz[SLORA_LN1_G], dh1_32,
-                                    nullptr, nullptr, nullptr, &tab, T, d, st)))
+                                    nullptr, nullptr, nullptr, tabp, T, d, st)))
                 return rc;
         }
     }
     c->state = 2;
+    return SLORA_OK;
+}
+
+int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, void *stream)
+{
+    if (!c || !dy || !h_dx_clients) return SLORA_EINVAL;
+    if (c->state != 1) return SLORA_ESTATE;
+    for (int i = 0; i < c->K; ++i)
+        if (!h_dx_clients[i] || (((uintptr_t)h_dx_clients[i]) & 7)) return SLORA_EINVAL;
+    if (((uintptr_t)dy) & 15) return SLORA_EINVAL;
+    ClientTable tab;
+    tab.K = c->K;
+    for (int i = 0; i < c->K; ++i) { tab.ptr[i] = h_dx_clients[i]; tab.row_end[i] = c->row_end[i]; }
+    return stack_bwd(c, dy, &tab, (hipStream_t)stream);
+}
+
+int slora_client_bwd(slora_ctx *c, const void *dact, void *stream)
+{
+    if (!c || !dact) return SLORA_EINVAL;
+    if (c->state != 1) return SLORA_ESTATE;
+    if (((uintptr_t)dact) & 15) return SLORA_EINVAL;
+    return stack_bwd(c, dact, nullptr, (hipStream_t)stream);
+}
+
+int slora_adapters_changed(slora_ctx *c)
+{
+    if (!c) return SLORA_EINVAL;
+    if (c->state == 1) return SLORA_ESTATE;      // between forward and backward the adapters must not move
+    c->shadows_dirty = true;
+    c->state = 0;
     return SLORA_OK;
 }
 

@@ -51,6 +51,14 @@ struct ClientTable {
     int K;
 };
 
+// Token + position embedding as the source of the first client-side block (row t of the input is
+// wte[tokens[t]] + wpe[t % seq_len]).
+struct EmbedSrc {
+    const int *tokens;             // [T]
+    const bf16 *wte, *wpe;         // [vocab, d], [>= seq_len, d]
+    int seq_len, vocab;
+};
+
 // ---- GEMM ---------------------------------------------------------------------------------
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_DGELU = 3 };
 
@@ -74,7 +82,7 @@ int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);
 // ---- elementwise / norm / attention / lora-grad launchers ---------------------------------------
 int launch_ln_fwd(const float *h_f32, const ClientTable *gather /*null unless block 0*/, float *h_copy,
                   const bf16 *gamma, const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d,
-                  hipStream_t st);
+                  hipStream_t st, const EmbedSrc *embed = nullptr);
 int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16 *gamma,
                   const float *dres_f32, const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16,
                   const ClientTable *scatter, int T, int d, hipStream_t st);

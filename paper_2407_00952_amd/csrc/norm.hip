@@ -6,7 +6,9 @@
 // These kernels are HBM-bound; they also carry the fp32 residual stream:
 //   forward : u = (h - mu) rho * gamma + beta  (bf16 out), stats (mu, rho) saved per row.
 //             For the first server block the input is gathered from the K client buffers
-//             (the concatenation S = [s_1; ...; s_N]) and an fp32 copy of it is kept.
+//             (the concatenation S = [s_1; ...; s_N]) and an fp32 copy of it is kept.  For the
+//             first CLIENT block the input is the token + position embedding, summed in fp32
+//             straight from the two frozen tables (client-side forward, Sec. III-B a1).
 //   backward: out = dres + rho (g - mean(g) - xhat mean(g xhat)),  g = du * gamma,
 //             written as fp32 (residual gradient) and/or bf16 (next GEMM operand, or the
 //             per-client activation gradient scattered back to the K client buffers).
@@ -24,21 +26,27 @@ __device__ __forceinline__ int client_of(const ClientTable &t, int row, int &loc
     return c;
 }
 
-template <bool GATHER>
-__global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h, ClientTable tab,
+// SRC 0: fp32 rows of h; 1: bf16 rows gathered from the client buffers; 2: embedding lookup
+template <int SRC>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h, ClientTable tab, EmbedSrc emb,
                                                      float *__restrict__ hcopy, const bf16 *__restrict__ gamma,
                                                      const bf16 *__restrict__ beta, float eps,
                                                      bf16 *__restrict__ u, float *__restrict__ stats, int T, int d)
 {
+    constexpr bool GATHER = SRC != 0;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= T) return;
     float v[MAXC][4];
-    const bf16 *src16 = nullptr;
-    if (GATHER) {
+    const bf16 *src16 = nullptr, *pos16 = nullptr;
+    if (SRC == 1) {
         int local;
         int c = client_of(tab, row, local);
         src16 = (const bf16 *)tab.ptr[c] + (size_t)local * d;
+    } else if (SRC == 2) {
+        const int tok = min(max(emb.tokens[row], 0), emb.vocab - 1);     // ids outside the table are clamped
+        src16 = emb.wte + (size_t)tok * d;
+        pos16 = emb.wpe + (size_t)(row % emb.seq_len) * d;
     }
     float s = 0.f;
 #pragma unroll
@@ -49,6 +57,11 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
                 bf16x4 t = *(const bf16x4 *)(src16 + col);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[c][i] = bf2f(t[i]);
+                if (SRC == 2) {
+                    bf16x4 q = *(const bf16x4 *)(pos16 + col);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[c][i] += bf2f(q[i]);
+                }
                 *(float4 *)(hcopy + (size_t)row * d + col) = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
             } else {
                 float4 t = *(const float4 *)(h + (size_t)row * d + col);
@@ -153,17 +166,23 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du
 }  // namespace
 
 int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, const bf16 *gamma,
-                  const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d, hipStream_t st)
+                  const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d, hipStream_t st,
+                  const EmbedSrc *embed)
 {
     if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
     dim3 grid((T + 3) / 4), block(256);
-    if (gather) {
-        hipLaunchKernelGGL((ln_fwd_kernel<true>), grid, block, 0, st, nullptr, *gather, h_copy, gamma, beta, eps, u,
+    ClientTable none;
+    none.K = 0;
+    EmbedSrc noemb = {nullptr, nullptr, nullptr, 1, 1};
+    if (embed) {
+        if (!embed->tokens || !embed->wte || !embed->wpe || embed->seq_len <= 0 || embed->vocab <= 0) return -1;
+        hipLaunchKernelGGL((ln_fwd_kernel<2>), grid, block, 0, st, nullptr, none, *embed, h_copy, gamma, beta, eps, u,
                            stats, T, d);
+    } else if (gather) {
+        hipLaunchKernelGGL((ln_fwd_kernel<1>), grid, block, 0, st, nullptr, *gather, noemb, h_copy, gamma, beta, eps,
+                           u, stats, T, d);
     } else {
-        ClientTable none;
-        none.K = 0;
-        hipLaunchKernelGGL((ln_fwd_kernel<false>), grid, block, 0, st, h_f32, none, nullptr, gamma, beta, eps, u,
+        hipLaunchKernelGGL((ln_fwd_kernel<0>), grid, block, 0, st, h_f32, none, noemb, nullptr, gamma, beta, eps, u,
                            stats, T, d);
     }
     SL_CHECK_LAUNCH("ln_fwd");
