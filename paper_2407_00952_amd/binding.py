@@ -261,16 +261,29 @@ class Server:
             self.frozen.append(dev)
             for k, t in dev.items():
                 slora_bind_frozen(self.ctx, l, FROZEN[k], t)
+        # adapters live in ONE flat fp32 vector (block by block, projections in PROJ order, A then B): that
+        # vector is what the aggregation of Eq. (8)-(9) averages; the gradients mirror the layout
+        n_par = sum(int(np.size(A)) + int(np.size(Bm)) for ad in adapters for (A, Bm) in ad.values())
+        self.flat = torch.empty(max(n_par, 1), dtype=torch.float32, device="cuda")
+        self.flat_grad = torch.zeros(max(n_par, 1), dtype=torch.float32, device="cuda")
         self.adapters = []
+        at = 0
         for l, ad in enumerate(adapters):
             dev = {}
-            for p, (A, B) in ad.items():
-                tA = torch.from_numpy(np.ascontiguousarray(A, dtype=np.float32)).cuda()
-                tB = torch.from_numpy(np.ascontiguousarray(B, dtype=np.float32)).cuda()
-                dA, dB = torch.zeros_like(tA), torch.zeros_like(tB)
+            for p in sorted(ad.keys(), key=lambda k: PROJ[k]):
+                A, Bm = ad[p]
+                views = []
+                for a in (A, Bm):
+                    a = np.ascontiguousarray(a, dtype=np.float32)
+                    v = self.flat[at:at + a.size].view(a.shape)
+                    v.copy_(torch.from_numpy(a))
+                    views.append((v, self.flat_grad[at:at + a.size].view(a.shape)))
+                    at += a.size
+                (tA, dA), (tB, dB) = views
                 dev[p] = (tA, tB, dA, dB)
                 slora_bind_adapter(self.ctx, l, PROJ[p], tA, tB, dA, dB)
             self.adapters.append(dev)
+        self.n_params = n_par
 
     def fwd(self, x_clients, y, stream=None):
         slora_server_fwd(self.ctx, x_clients, [t.shape[0] for t in x_clients], y, stream)
@@ -280,6 +293,9 @@ class Server:
 
     def step(self, lr, stream=None):
         slora_adapter_step(self.ctx, lr, stream)
+
+    def adapters_changed(self):
+        slora_adapters_changed(self.ctx)
 
     def close(self):
         if self.ctx is not None:
@@ -291,3 +307,14 @@ class Server:
             self.close()
         except Exception:
             pass
+
+
+class Client(Server):
+    """One client's share of the model: embedding + its blocks with its own adapters (same C ABI context
+    type as the server; the frozen tables wte / wpe are shared device tensors owned by the caller)."""
+
+    def fwd(self, tokens, vocab, wte, wpe, act, stream=None):
+        slora_client_fwd(self.ctx, act.shape[0], tokens, vocab, wte, wpe, act, stream)
+
+    def bwd(self, dact, stream=None):
+        slora_client_bwd(self.ctx, dact, stream)
