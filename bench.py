@@ -162,6 +162,34 @@ def main():
     lh_ms = (time.perf_counter() - t1) / 5 * 1e3
     lh_flop = 4.0 * cfg.tokens * cfg.d_model * V
 
+    # one client's share of a round (embedding + client-side blocks forward, backward, SGD step), on its own
+    import dataclasses
+    n_cb = synth.FEDAVG_CLIENT_BLOCKS
+    c_cfg = dataclasses.replace(cfg, n_blocks=n_cb)
+    c_inp = synth.make_stack_inputs(dataclasses.replace(c_cfg, n_clients=1, seed=cfg.seed + 7000), with_dy=False)
+    cl = B.Client(c_cfg, c_inp["blocks"], c_inp["adapters"], max_seqs=cfg.batch)
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 7001))
+    cl_tok = torch.from_numpy(rng.integers(0, V, size=(cfg.batch, cfg.seq_len)).astype(np.int32)).cuda()
+    cl_wpe = B.to_device_bf16(synth.round_bf16(rng.standard_normal((cfg.seq_len, cfg.d_model), dtype=np.float32)
+                                               * np.float32(0.02)))
+    cl_act = torch.empty((cfg.batch, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    cl_dact = dy[:cfg.batch].contiguous()
+
+    def client_round():
+        cl.fwd(cl_tok, V, lh_Wv, cl_wpe, cl_act, stream)
+        cl.bwd(cl_dact, stream)
+        cl.step(lr, stream)
+
+    for _ in range(2):
+        client_round()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(10):
+        client_round()
+    torch.cuda.synchronize()
+    cl_ms = (time.perf_counter() - t2) / 10 * 1e3
+    del cl
+
     if args.copy_calibration:
         n_cal = 64 * 1024 * 1024
         src = torch.ones(n_cal, dtype=torch.float32, device="cuda")
@@ -194,6 +222,9 @@ def main():
                      "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
                      "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
     }
+    out["client_side"] = {"ms": cl_ms, "client_blocks": n_cb, "tokens": cfg.batch * cfg.seq_len,
+                          "tokens_per_s": cfg.batch * cfg.seq_len / (cl_ms * 1e-3),
+                          "what": "one client: embedding + client blocks forward, backward, SGD step"}
     out["loss_head"] = {"ms": lh_ms, "vocab": V, "tflops": lh_flop / (lh_ms * 1e-3) / 1e12,
                         "in_timed_step": bool(args.loss_head)}
     if not args.no_cpu_baseline:
