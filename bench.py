@@ -83,6 +83,8 @@ def main():
                     help="put the loss head (final LayerNorm, vocabulary logits, cross-entropy -> dY) between "
                          "forward and backward inside the timed step; without it the step takes dY as given and "
                          "the loss head is timed on its own after the timed region")
+    ap.add_argument("--no-legs", action="store_true",
+                    help="skip the separately timed loss-head and client-side legs (profiles of the metric's step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps, run a plain copy of known size (FedAvg with one client, "
                          "256 MiB in, 256 MiB out) so that HBM byte counters can be scaled")
@@ -113,17 +115,18 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     # loss head: GPT-2's vocabulary, labels with a context part that carries no label
     V = synth.GPT2_VOCAB
-    lh = synth.make_loss_head_inputs(cfg.n_seq, cfg.seq_len, cfg.d_model, vocab=V)
-    lh_bytes = B.slora_loss_head_ws_bytes(cfg.tokens, cfg.d_model, V)
-    lh_ws = torch.empty(lh_bytes, dtype=torch.uint8, device="cuda")
-    lh_Wv = B.to_device_bf16(lh["Wv"])
-    B.slora_loss_head_prepare(cfg.d_model, V, lh_Wv, lh_ws, lh_bytes, stream)
-    lh_g, lh_b = B.to_device_bf16(lh["lnf_g"]), B.to_device_bf16(lh["lnf_b"])
-    lh_labels = torch.from_numpy(lh["labels"]).cuda()
-    lh_tok = torch.empty(cfg.tokens, dtype=torch.float32, device="cuda")
-    lh_loss = torch.empty(1, dtype=torch.float32, device="cuda")
-    lh_dy = torch.empty_like(dy)
-    del lh
+    if not args.no_legs or args.loss_head:
+        lh = synth.make_loss_head_inputs(cfg.n_seq, cfg.seq_len, cfg.d_model, vocab=V)
+        lh_bytes = B.slora_loss_head_ws_bytes(cfg.tokens, cfg.d_model, V)
+        lh_ws = torch.empty(lh_bytes, dtype=torch.uint8, device="cuda")
+        lh_Wv = B.to_device_bf16(lh["Wv"])
+        B.slora_loss_head_prepare(cfg.d_model, V, lh_Wv, lh_ws, lh_bytes, stream)
+        lh_g, lh_b = B.to_device_bf16(lh["lnf_g"]), B.to_device_bf16(lh["lnf_b"])
+        lh_labels = torch.from_numpy(lh["labels"]).cuda()
+        lh_tok = torch.empty(cfg.tokens, dtype=torch.float32, device="cuda")
+        lh_loss = torch.empty(1, dtype=torch.float32, device="cuda")
+        lh_dy = torch.empty_like(dy)
+        del lh
 
     def loss_head():
         B.slora_loss_head(cfg.tokens, cfg.d_model, V, y, lh_g, lh_b, cfg.ln_eps, lh_labels, lh_ws, lh_bytes, lh_tok,
@@ -152,43 +155,47 @@ def main():
     B.slora_prof_enable(0)
 
     # the loss head on its own (outside the timed region and outside the GEMM statistics above)
-    for _ in range(2):
-        loss_head()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(5):
-        loss_head()
-    torch.cuda.synchronize()
-    lh_ms = (time.perf_counter() - t1) / 5 * 1e3
+    legs = not args.no_legs
+    lh_ms = cl_ms = float("nan")
+    if legs:
+        for _ in range(2):
+            loss_head()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(5):
+            loss_head()
+        torch.cuda.synchronize()
+        lh_ms = (time.perf_counter() - t1) / 5 * 1e3
     lh_flop = 4.0 * cfg.tokens * cfg.d_model * V
 
     # one client's share of a round (embedding + client-side blocks forward, backward, SGD step), on its own
-    import dataclasses
     n_cb = synth.FEDAVG_CLIENT_BLOCKS
-    c_cfg = dataclasses.replace(cfg, n_blocks=n_cb)
-    c_inp = synth.make_stack_inputs(dataclasses.replace(c_cfg, n_clients=1, seed=cfg.seed + 7000), with_dy=False)
-    cl = B.Client(c_cfg, c_inp["blocks"], c_inp["adapters"], max_seqs=cfg.batch)
-    rng = np.random.Generator(np.random.PCG64(cfg.seed + 7001))
-    cl_tok = torch.from_numpy(rng.integers(0, V, size=(cfg.batch, cfg.seq_len)).astype(np.int32)).cuda()
-    cl_wpe = B.to_device_bf16(synth.round_bf16(rng.standard_normal((cfg.seq_len, cfg.d_model), dtype=np.float32)
-                                               * np.float32(0.02)))
-    cl_act = torch.empty((cfg.batch, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
-    cl_dact = dy[:cfg.batch].contiguous()
+    if legs:
+        import dataclasses
+        c_cfg = dataclasses.replace(cfg, n_blocks=n_cb)
+        c_inp = synth.make_stack_inputs(dataclasses.replace(c_cfg, n_clients=1, seed=cfg.seed + 7000), with_dy=False)
+        cl = B.Client(c_cfg, c_inp["blocks"], c_inp["adapters"], max_seqs=cfg.batch)
+        rng = np.random.Generator(np.random.PCG64(cfg.seed + 7001))
+        cl_tok = torch.from_numpy(rng.integers(0, V, size=(cfg.batch, cfg.seq_len)).astype(np.int32)).cuda()
+        cl_wpe = B.to_device_bf16(synth.round_bf16(rng.standard_normal((cfg.seq_len, cfg.d_model), dtype=np.float32)
+                                                   * np.float32(0.02)))
+        cl_act = torch.empty((cfg.batch, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+        cl_dact = dy[:cfg.batch].contiguous()
 
-    def client_round():
-        cl.fwd(cl_tok, V, lh_Wv, cl_wpe, cl_act, stream)
-        cl.bwd(cl_dact, stream)
-        cl.step(lr, stream)
+        def client_round():
+            cl.fwd(cl_tok, V, lh_Wv, cl_wpe, cl_act, stream)
+            cl.bwd(cl_dact, stream)
+            cl.step(lr, stream)
 
-    for _ in range(2):
-        client_round()
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for _ in range(10):
-        client_round()
-    torch.cuda.synchronize()
-    cl_ms = (time.perf_counter() - t2) / 10 * 1e3
-    del cl
+        for _ in range(2):
+            client_round()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(10):
+            client_round()
+        torch.cuda.synchronize()
+        cl_ms = (time.perf_counter() - t2) / 10 * 1e3
+        del cl
 
     if args.copy_calibration:
         n_cal = 64 * 1024 * 1024
@@ -222,11 +229,12 @@ def main():
                      "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
                      "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
     }
-    out["client_side"] = {"ms": cl_ms, "client_blocks": n_cb, "tokens": cfg.batch * cfg.seq_len,
-                          "tokens_per_s": cfg.batch * cfg.seq_len / (cl_ms * 1e-3),
-                          "what": "one client: embedding + client blocks forward, backward, SGD step"}
-    out["loss_head"] = {"ms": lh_ms, "vocab": V, "tflops": lh_flop / (lh_ms * 1e-3) / 1e12,
-                        "in_timed_step": bool(args.loss_head)}
+    if legs:
+        out["client_side"] = {"ms": cl_ms, "client_blocks": n_cb, "tokens": cfg.batch * cfg.seq_len,
+                              "tokens_per_s": cfg.batch * cfg.seq_len / (cl_ms * 1e-3),
+                              "what": "one client: embedding + client blocks forward, backward, SGD step"}
+        out["loss_head"] = {"ms": lh_ms, "vocab": V, "tflops": lh_flop / (lh_ms * 1e-3) / 1e12,
+                            "in_timed_step": bool(args.loss_head)}
     if not args.no_cpu_baseline:
         del srv
         torch.cuda.empty_cache()

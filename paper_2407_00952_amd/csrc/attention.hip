@@ -29,7 +29,12 @@ typedef short v4s __attribute__((ext_vector_type(4)));
                                      (__attribute__((address_space(3))) void *)(lp), 16, 0, 0)
 #define AT_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
-__device__ __forceinline__ int swz128(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+// XOR mask of a tile row for the 16-byte chunks of its 128-byte LDS row.  Eight consecutive rows get
+// eight different masks (row-major fragment reads: 8 lanes = 8 rows, one logical chunk), and four
+// consecutive rows get masks that differ in bits 1-2 (transpose reads: 16 lanes = 4 rows x 2 adjacent
+// chunks), so both kinds of operand read are bank-conflict free.
+__device__ __forceinline__ int swm(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+__device__ __forceinline__ int swz128(int row, int chunk) { return row * 128 + ((chunk ^ swm(row)) << 4); }
 
 __device__ __forceinline__ f32x16 zero16()
 {
@@ -43,7 +48,7 @@ __device__ __forceinline__ f32x16 zero16()
 // Four waves, two 1 KB pieces (8 rows) each: lane l fills slot l = (row l>>3, physical chunk l&7).
 __device__ __forceinline__ void tile_copy_async(unsigned char *dst, const bf16 *src, int ld, int wave, int lane)
 {
-    const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
+    const int lrow = lane >> 3, lch = (lane & 7) ^ swm(lane >> 3);
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const int r0 = (wave * 2 + p) * 8;
@@ -66,8 +71,8 @@ __device__ __forceinline__ bf16x8 frag_tr(const unsigned char *t, int col0, int 
     const int q = lane & 3, e = (lane >> 2) & 3, half = (lane >> 4) & 1, g = lane >> 5;
     const int col = col0 + 16 * half + 4 * q;
     const int row0 = tok0 + 4 * g + e, row1 = row0 + 8;
-    const unsigned char *a0 = t + row0 * 128 + (((col >> 3) ^ (row0 & 7)) << 4) + (col & 7) * 2;
-    const unsigned char *a1 = t + row1 * 128 + (((col >> 3) ^ (row1 & 7)) << 4) + (col & 7) * 2;
+    const unsigned char *a0 = t + row0 * 128 + (((col >> 3) ^ swm(row0)) << 4) + (col & 7) * 2;
+    const unsigned char *a1 = t + row1 * 128 + (((col >> 3) ^ swm(row1)) << 4) + (col & 7) * 2;
     union { v4s s[2]; bf16x8 v; } u;
     u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)a0);
     u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)a1);

@@ -43,9 +43,9 @@ def main(fetch_csv, write_csv):
     print("# HBM traffic of the bf16 GEMM kernel, workload 3 (rocprofv3 counters)\n")
     print("Commands (from /tmp with TMPDIR=/tmp, one counter per run):\n")
     print("    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_fetch -o f -- "
-          "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --copy-calibration")
+          "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-legs --copy-calibration")
     print("    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_write -o w -- "
-          "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --copy-calibration")
+          "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-legs --copy-calibration")
     print("    python -m paper_2407_00952_amd.pmc_summary <f_counter_collection.csv> <w_counter_collection.csv>\n")
     print("| counter | copy kernel reads (256 MiB moved) | bytes per count | GEMM launches | GEMM average count | GEMM bytes per launch |")
     print("|---|---|---|---|---|---|")

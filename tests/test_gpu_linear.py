@@ -97,6 +97,8 @@ def test_fp32_zero_B_is_bitwise_base():
     (256, 64, 64, 16, True),         # one tile, full rank
     (1300, 1024, 3072, 8, True),     # several column tiles
     (64, 128, 128, 1, False),
+    (512, 768, 768, 2, True),        # the remaining ranks of the paper's sweep r in {1, 2, 4, 8} (Sec. IV)
+    (512, 768, 2304, 8, False),
 ])
 def test_bf16_layer(T, n_in, n_out, r, bias):
     c = synth.make_single_layer(T, n_in, n_out, r, seed=100 + T + r, quant=True, bias=bias)
