@@ -42,10 +42,12 @@ def main(fetch_csv, write_csv):
     total = out["FETCH_SIZE"]["bytes"] + out["WRITE_SIZE"]["bytes"]
     print("# HBM traffic of the bf16 GEMM kernel, workload 3 (rocprofv3 counters)\n")
     print("Commands (from /tmp with TMPDIR=/tmp, one counter per run):\n")
-    print("    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_fetch -o f -- "
-          "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-legs --copy-calibration")
-    print("    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_write -o w -- "
-          "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-legs --copy-calibration")
+    for counter, path in (("FETCH_SIZE", fetch_csv), ("WRITE_SIZE", write_csv)):
+        outdir = os.path.dirname(path) or "."
+        prefix = os.path.basename(path).replace("_counter_collection.csv", "")
+        print("    rocprofv3 --pmc %s --kernel-trace --output-format csv -d %s -o %s -- "
+              "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-legs --copy-calibration"
+              % (counter, outdir, prefix))
     print("    python -m paper_2407_00952_amd.pmc_summary <f_counter_collection.csv> <w_counter_collection.csv>\n")
     print("| counter | copy kernel reads (256 MiB moved) | bytes per count | GEMM launches | GEMM average count | GEMM bytes per launch |")
     print("|---|---|---|---|---|---|")
