@@ -25,6 +25,13 @@ SMALL = {
     "rank1-k-fc-pr": synth.tiny_config(d_model=192, n_head=3, d_ff=320, n_blocks=3, lora_r=1,
                                        lora_proj=("k", "fc", "pr"), n_clients=2, batch=2, seq_len=128,
                                        seed=synth.BASE_SEED + 104),
+    # the limits of the library: widest and narrowest model it accepts (d_model 2048 and 64)
+    "widest-d2048": synth.tiny_config(d_model=2048, n_head=32, d_ff=2112, n_blocks=1, lora_r=4,
+                                      lora_proj=("q", "v", "fc"), n_clients=1, batch=2, seq_len=64,
+                                      seed=synth.BASE_SEED + 107),
+    "narrowest-d64": synth.tiny_config(d_model=64, n_head=1, d_ff=64, n_blocks=2, lora_r=4,
+                                       lora_proj=("q", "o", "pr"), n_clients=2, batch=1, seq_len=64,
+                                       seed=synth.BASE_SEED + 108),
     # the paper sweeps the rank over {1, 2, 4, 8} (Sec. IV): r = 2 and r = 8 on the paper's (q, v) placement
     "rank2-qv": synth.tiny_config(d_model=128, n_head=2, d_ff=256, n_blocks=2, lora_r=2, lora_proj=("q", "v"),
                                   n_clients=2, batch=1, seq_len=128, seed=synth.BASE_SEED + 105),
