@@ -104,6 +104,18 @@ int slora_server_bwd(slora_ctx *ctx, const void *dy, void *const *h_dx_clients, 
 /* Eq. (4),(5): p = fmaf(-lr, g, p) on every bound A, B; legal only after a backward. */
 int slora_adapter_step(slora_ctx *ctx, float lr, void *stream);
 
+/* ---- optimiser variant: AdamW on a flat parameter vector -------------------------------------------
+ * The paper's updates (Eq. 4-7) are plain SGD = slora_adapter_step.  For callers that fine-tune with
+ * Adam and decoupled weight decay instead, this applies one step to n fp32 parameters p with gradient g
+ * and moment vectors m, v (all device pointers, caller-owned, m = v = 0 before step 1), in the order
+ *   p *= 1 - lr*wd;  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+ *   p -= lr/(1-b1^step) * m / (sqrt(v)/sqrt(1-b2^step) + eps)
+ * evaluated in fp32 with one fixed operation order (bit-reproducible).  When p is the memory bound to a
+ * context as its adapters (after slora_server_bwd / slora_client_bwd), follow it with
+ * slora_adapters_changed instead of slora_adapter_step.  step >= 1, 0 <= beta < 1, eps > 0. */
+int slora_adamw(size_t n, float *p, const float *g, float *m, float *v, float lr, float beta1, float beta2,
+                float eps, float weight_decay, int32_t step, void *stream);
+
 /* ---- client-adapter aggregation (Sec. III-B b2, Eq. 8-9) -------------------------------------- */
 /* out[j] = sum_i w_i x_i[j] over K flat fp32 vectors of n floats, with
  * w_i = (float)((double)n_i / (double)sum n) and the fixed evaluation order

@@ -60,3 +60,16 @@ def sgd_f32(p, g, lr):
     _load().oracle_sgd_f32(out.ctypes.data_as(ctypes.c_void_p), g.ctypes.data_as(ctypes.c_void_p),
                            ctypes.c_float(lr), ctypes.c_size_t(out.size))
     return out.reshape(np.shape(p))
+
+
+def adamw_f32(p, g, m, v, lr, beta1, beta2, eps, weight_decay, step):
+    """Fixed-order fp32 AdamW step on flat vectors; returns new (p, m, v)."""
+    p = np.ascontiguousarray(p, dtype=np.float32).copy().ravel()
+    m = np.ascontiguousarray(m, dtype=np.float32).copy().ravel()
+    v = np.ascontiguousarray(v, dtype=np.float32).copy().ravel()
+    g = np.ascontiguousarray(g, dtype=np.float32).ravel()
+    vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    _load().oracle_adamw_f32(vp(p), vp(g), vp(m), vp(v), ctypes.c_size_t(p.size), ctypes.c_float(lr),
+                             ctypes.c_float(beta1), ctypes.c_float(beta2), ctypes.c_float(eps),
+                             ctypes.c_float(weight_decay), ctypes.c_int(step))
+    return p, m, v

@@ -6,6 +6,11 @@
  *     w_i = (float)((double)n_i / (double)sum_j n_j)
  *     acc = 0.0f;  for i = 0 .. K-1 in client order:  acc = fmaf(w_i, x_i[j], acc)
  * Eq. (4)-(5), the SGD update, in the same spirit:  p = fmaf(-lr, g, p).
+ * The AdamW variant (not in the paper) in one stated order, host scalars in double:
+ *     decay = (float)(1 - lr*wd), a = (float)(lr / (1 - b1^t)), c = (float)(1 / sqrt(1 - b2^t)),
+ *     o1 = (float)(1 - b1), o2 = (float)(1 - b2);
+ *     m = fmaf(b1, m, o1*g);  v = fmaf(b2, v, (o2*g)*g);
+ *     p = fmaf(-a, m / fmaf(sqrtf(v), c, eps), p*decay).
  *
  * Built by gcc into libslora_oracle_c.so; shares nothing with the HIP sources.
  */
@@ -37,4 +42,27 @@ void oracle_fedavg_f32(int K, const float *const *x, const float *w, size_t n, f
 void oracle_sgd_f32(float *p, const float *g, float lr, size_t n)
 {
     for (size_t j = 0; j < n; ++j) p[j] = fmaf(-lr, g[j], p[j]);
+}
+
+void oracle_adamw_f32(float *p, const float *g, float *m, float *v, size_t n, float lr, float b1, float b2,
+                      float eps, float wd, int step)
+{
+    const float decay = (float)(1.0 - (double)lr * (double)wd);
+    const float a = (float)((double)lr / (1.0 - pow((double)b1, (double)step)));
+    const float c = (float)(1.0 / sqrt(1.0 - pow((double)b2, (double)step)));
+    const float o1 = (float)(1.0 - (double)b1), o2 = (float)(1.0 - (double)b2);
+    for (size_t j = 0; j < n; ++j) {
+        const float gj = g[j];
+        const float t1 = o1 * gj;
+        const float mj = fmaf(b1, m[j], t1);
+        const float t2 = o2 * gj;
+        const float t3 = t2 * gj;
+        const float vj = fmaf(b2, v[j], t3);
+        const float den = fmaf(sqrtf(vj), c, eps);
+        const float q = mj / den;
+        const float pd = p[j] * decay;
+        p[j] = fmaf(-a, q, pd);
+        m[j] = mj;
+        v[j] = vj;
+    }
 }

@@ -332,3 +332,19 @@ def fedavg(client_params, sample_counts):
     for ni, x in zip(n, client_params):
         out = out + (ni / tot) * _f64(x)
     return out
+
+
+# ----------------------------------------------------------------------------------
+# Optimiser variant (not in the paper, whose Eq. 4-7 are plain SGD): Adam with decoupled
+# weight decay (Loshchilov & Hutter), in the order torch.optim.AdamW applies it.
+# ----------------------------------------------------------------------------------
+def adamw_step(p, g, m, v, lr, beta1, beta2, eps, weight_decay, step):
+    """One update of the flat vectors; step counts from 1.  Returns (p, m, v)."""
+    p, g, m, v = _f64(p), _f64(g), _f64(m), _f64(v)
+    p = p * (1.0 - lr * weight_decay)
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    bc1 = 1.0 - beta1 ** step
+    bc2 = 1.0 - beta2 ** step
+    p = p - (lr / bc1) * m / (np.sqrt(v) / math.sqrt(bc2) + eps)
+    return p, m, v

@@ -28,7 +28,7 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error", "slora_prof_enable",
            "slora_prof_read", "slora_frozen_linear_bf16", "slora_loss_head_ws_bytes",
            "slora_loss_head_prepare", "slora_loss_head", "slora_client_fwd", "slora_client_bwd",
-           "slora_adapters_changed"]
+           "slora_adapters_changed", "slora_adamw"]
 
 
 class slora_config(ctypes.Structure):
@@ -74,6 +74,7 @@ def lib():
         L.slora_client_fwd.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
         L.slora_client_bwd.argtypes = [vp, vp, vp]
         L.slora_adapters_changed.argtypes = [vp]
+        L.slora_adamw.argtypes = [sz, vp, vp, vp, vp, f32, f32, f32, f32, f32, i32, vp]
         L.slora_loss_head_ws_bytes.argtypes = [i32, i32, i32]
         L.slora_loss_head_ws_bytes.restype = sz
         L.slora_loss_head_prepare.argtypes = [i32, i32, vp, vp, sz, vp]
@@ -195,6 +196,11 @@ def slora_client_bwd(ctx, dact, stream=None):
 
 def slora_adapters_changed(ctx):
     _check(lib().slora_adapters_changed(ctx))
+
+
+def slora_adamw(n, p, g, m, v, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _check(lib().slora_adamw(n, _p(p), _p(g), _p(m), _p(v), lr, beta1, beta2, eps, weight_decay, step,
+                             _stream(stream)))
 
 
 def slora_loss_head_ws_bytes(max_tokens, d_model, vocab):

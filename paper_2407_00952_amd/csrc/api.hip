@@ -6,6 +6,7 @@
 #include "common.h"
 
 #include <array>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -689,6 +690,20 @@ int slora_fedavg(int K, const float *const *h_client_params, const int64_t *h_sa
     float w[SLORA_MAX_CLIENTS];
     for (int i = 0; i < K; ++i) w[i] = (float)((double)h_sample_counts[i] / tot);
     return launch_fedavg(K, h_client_params, w, n, out, (hipStream_t)stream);
+}
+
+int slora_adamw(size_t n, float *p, const float *g, float *m, float *v, float lr, float beta1, float beta2, float eps,
+                float weight_decay, int32_t step, void *stream)
+{
+    if (!p || !g || !m || !v) return SLORA_EINVAL;
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps > 0.f) || !(lr == lr) ||
+        !(weight_decay == weight_decay))
+        return SLORA_EINVAL;
+    const float decay = (float)(1.0 - (double)lr * (double)weight_decay);
+    const float a = (float)((double)lr / (1.0 - pow((double)beta1, (double)step)));
+    const float c = (float)(1.0 / sqrt(1.0 - pow((double)beta2, (double)step)));
+    const float o1 = (float)(1.0 - (double)beta1), o2 = (float)(1.0 - (double)beta2);
+    return launch_adamw(p, g, m, v, n, beta1, beta2, eps, decay, a, c, o1, o2, (hipStream_t)stream);
 }
 
 // ---- single layer -----------------------------------------------------------------------------

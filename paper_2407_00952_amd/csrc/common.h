@@ -95,6 +95,8 @@ int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int 
 size_t lora_grad_partial_floats(int T, int C);
 int launch_fedavg(int K, const float *const *x, const float *w, size_t n, float *out, hipStream_t st);
 int launch_sgd(float *p, const float *g, float lr, size_t n, hipStream_t st);
+int launch_adamw(float *p, const float *g, float *m, float *v, size_t n, float b1, float b2, float eps, float decay,
+                 float a, float c, float o1, float o2, hipStream_t st);
 int launch_cast_pad(const float *src, int rows, int cols, bf16 *dst, int drows, int dcols, int transpose,
                     hipStream_t st);
 int launch_transpose_bf16(const bf16 *src, int rows, int cols, bf16 *dst, hipStream_t st);

@@ -188,6 +188,34 @@ __global__ __launch_bounds__(256) void sgd_kernel(float *__restrict__ p, const f
     for (; i < n; i += stride) p[i] = __fmaf_rn(-lr, g[i], p[i]);
 }
 
+// AdamW variant of the adapter update (the paper's Eq. 4-7 are plain SGD; this is the usual Adam rule
+// with decoupled weight decay, in one fixed evaluation order so that results are bit-reproducible):
+//   m = fmaf(b1, m, o1*g);  v = fmaf(b2, v, (o2*g)*g);  p = fmaf(-a, m / fmaf(sqrtf(v), c, eps), p*decay)
+// with the scalars decay, a, c, o1, o2 prepared on the host in double precision.
+__global__ __launch_bounds__(256) void adamw_kernel(float *__restrict__ p, const float *__restrict__ g,
+                                                    float *__restrict__ m, float *__restrict__ v, size_t n, float b1,
+                                                    float b2, float eps, float decay, float a, float c, float o1,
+                                                    float o2)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n; i += stride) {
+        const float gj = g[i];
+        const float t1 = o1 * gj;
+        const float mj = __fmaf_rn(b1, m[i], t1);
+        const float t2 = o2 * gj;
+        const float t3 = t2 * gj;
+        const float vj = __fmaf_rn(b2, v[i], t3);
+        // plain sqrtf and / are the correctly rounded ones (the compiler's default for fp32 in device code)
+        const float den = __fmaf_rn(sqrtf(vj), c, eps);
+        const float q = mj / den;
+        const float pd = p[i] * decay;
+        p[i] = __fmaf_rn(-a, q, pd);
+        m[i] = mj;
+        v[i] = vj;
+    }
+}
+
 // src fp32 [rows, cols] -> dst bf16 [drows, dcols], zero padded; optionally transposed first
 __global__ __launch_bounds__(256) void cast_pad_kernel(const float *__restrict__ src, int rows, int cols,
                                                        bf16 *__restrict__ dst, int drows, int dcols, int transpose)
@@ -298,6 +326,18 @@ int launch_sgd(float *p, const float *g, float lr, size_t n, hipStream_t st)
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, g, lr, n);
     SL_CHECK_LAUNCH("sgd");
+    return 0;
+}
+
+int launch_adamw(float *p, const float *g, float *m, float *v, size_t n, float b1, float b2, float eps, float decay,
+                 float a, float c, float o1, float o2, hipStream_t st)
+{
+    if (n == 0) return 0;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, g, m, v, n, b1, b2, eps, decay, a, c,
+                       o1, o2);
+    SL_CHECK_LAUNCH("adamw");
     return 0;
 }
 

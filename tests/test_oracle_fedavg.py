@@ -109,3 +109,41 @@ def test_sgd_f32_is_one_fma_per_element():
 def test_workload5_adapter_vector_size():
     # 6 client blocks, r = 16, six projections of GPT-2-medium: 294 912 floats per block
     assert synth.fedavg_param_count(synth.CONFIGS[5]) == 6 * 294912 == 1769472
+
+
+# ---- AdamW variant of the adapter step (beyond the paper's plain SGD) ------------------------------
+def test_adamw_oracle_matches_torch_optimizer():
+    import torch
+    rng = np.random.default_rng(11)
+    p0 = rng.standard_normal(257)
+    hp = dict(lr=3e-3, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1)
+    tp = torch.tensor(p0.copy(), dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([tp], **hp)
+    p, m, v = p0.copy(), np.zeros_like(p0), np.zeros_like(p0)
+    for step in range(1, 6):
+        g = rng.standard_normal(257) * (0.1 if step % 2 else 3.0)
+        tp.grad = torch.tensor(g.copy(), dtype=torch.float64)
+        opt.step()
+        p, m, v = so.adamw_step(p, g, m, v, hp["lr"], hp["betas"][0], hp["betas"][1], hp["eps"],
+                                hp["weight_decay"], step)
+        assert np.allclose(p, tp.detach().numpy(), rtol=1e-12, atol=1e-14), step
+
+
+def test_adamw_fixed_order_f32_close_to_oracle_and_first_step_closed_form():
+    rng = np.random.default_rng(12)
+    n = 1000
+    p0 = rng.standard_normal(n).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    z = np.zeros(n, dtype=np.float32)
+    p1, m1, v1 = cref.adamw_f32(p0, g, z, z, 1e-2, 0.9, 0.999, 1e-8, 0.0, 1)
+    # first step, no decay: m/(1-b1) = g, v/(1-b2) = g^2, so p moves by lr * sign(g) (up to eps)
+    assert np.allclose(p1, p0 - 1e-2 * np.sign(g), rtol=0, atol=2e-7)
+    p, m, v = p0.astype(np.float64), np.zeros(n), np.zeros(n)
+    pf, mf, vf = p0, z, z
+    for step in range(1, 5):
+        gs = (rng.standard_normal(n) * 0.5).astype(np.float32)
+        p, m, v = so.adamw_step(p, gs, m, v, 2e-3, 0.9, 0.98, 1e-6, 0.05, step)
+        pf, mf, vf = cref.adamw_f32(pf, gs, mf, vf, 2e-3, 0.9, 0.98, 1e-6, 0.05, step)
+    assert np.abs(pf - p).max() <= 2e-6 * np.abs(p).max()
+    assert np.abs(mf - m).max() <= 2e-6 * np.abs(m).max()
+    assert np.abs(vf - v).max() <= 2e-6 * np.abs(v).max()
