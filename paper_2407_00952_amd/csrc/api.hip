@@ -597,11 +597,29 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.K2 = c->k2_qkv; a.ldt = c->k2p_qkv;
             }
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? c->nz_qkv : 0, st))) return rc;
+            // dB per adapted projection (its own slice of dq|dk|dv against its own zs); dA for the adapters
+            // two at a time: they share the operand u, and their rank-space gradients sit side by side in ps
+            float *part = at<float>(c, c->t_part);
+            int slot_proj[3], nslot = 0;
             for (int p = 0; p < 3; ++p)
-                if (adapted(c, p) &&
-                    (rc = lora_grads(c, l, p, at<bf16>(c, b.u), d, dqkv + (size_t)p * d, 3 * d,
-                                     ps + 16 * c->qkv_idx[p], c->k2_qkv, st)))
-                    return rc;
+                if (adapted(c, p)) {
+                    slot_proj[c->qkv_idx[p]] = p;
+                    ++nslot;
+                    if ((rc = launch_lora_grad(dqkv + (size_t)p * d, 3 * d, d, at<bf16>(c, b.zs[p]), SL_RP, c->r, T, part,
+                                               c->adapters[l][p].dB, 0, st)))
+                        return rc;
+                }
+            for (int sl = 0; sl < nslot; sl += 2) {
+                const bf16 *ys = ps + 16 * sl;
+                if (sl + 1 < nslot)
+                    rc = launch_lora_grad_pair(at<bf16>(c, b.u), d, d, ys, c->k2_qkv, c->r, T, part,
+                                               c->adapters[l][slot_proj[sl]].dA, c->adapters[l][slot_proj[sl + 1]].dA, 1,
+                                               st);
+                else
+                    rc = launch_lora_grad(at<bf16>(c, b.u), d, d, ys, c->k2_qkv, c->r, T, part,
+                                          c->adapters[l][slot_proj[sl]].dA, 1, st);
+                if (rc) return rc;
+            }
         }
         // dh = dh' + LN1^T(du): next block's incoming gradient, or the clients' activation gradients
         float *nx32 = at<float>(c, c->t_dh32[0]);

@@ -92,6 +92,8 @@ int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16
 // G[c, j] = sum_t X[t, c] * Y[t, j], j < r; written transposed ([r, C]) when out_is_rxC.
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T,
                      float *partials, float *out, int out_is_rxC, hipStream_t st);
+int launch_lora_grad_pair(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T,
+                          float *partials, float *out_a, float *out_b, int out_is_rxC, hipStream_t st);
 size_t lora_grad_partial_floats(int T, int C);
 int launch_fedavg(int K, const float *const *x, const float *w, size_t n, float *out, hipStream_t st);
 int launch_sgd(float *p, const float *g, float lr, size_t n, hipStream_t st);

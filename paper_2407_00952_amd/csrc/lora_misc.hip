@@ -39,27 +39,35 @@ __device__ __forceinline__ bf16x8 xfrag_tr(const unsigned char *t, int col0, int
     u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)a1);
     return u.v;
 }
-// Y tile: [64 tokens][16] bf16, 32-byte rows, no swizzle; every lane group reads columns 0..15 (the
-// MFMA columns 16..31 then hold copies that are never stored)
+// Y tile: [64 tokens][16] bf16 in 32-byte rows (every lane group reads columns 0..15; the MFMA columns
+// 16..31 then hold copies that are never stored), or, for two adapters at once, [64][32] bf16 in rows of
+// 96 bytes (64 used): with that pitch the four rows one read touches fall into different banks.
+template <bool DUAL>
 __device__ __forceinline__ bf16x8 yfrag_tr(const unsigned char *t, int tok0, int lane)
 {
-    const int q = lane & 3, e = (lane >> 2) & 3, g = lane >> 5;
+    constexpr int YP = DUAL ? 96 : 32;
+    const int q = lane & 3, e = (lane >> 2) & 3, half = (lane >> 4) & 1, g = lane >> 5;
     const int row0 = tok0 + 4 * g + e, row1 = row0 + 8;
+    const int co = (DUAL ? half * 32 : 0) + q * 8;
     union { v4s_t s[2]; bf16x8 v; } u;
-    u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)(t + row0 * 32 + q * 8));
-    u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)(t + row1 * 32 + q * 8));
+    u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)(t + row0 * YP + co));
+    u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t *)(t + row1 * YP + co));
     return u.v;
 }
 
 // partial[chunk][j][c] = sum over the chunk's tokens of X[t,c] * Y[t,j]  on the matrix cores:
 // D[m = c][n = j] += X^T[c][t] * Y[t][j], both operands read along the token axis with the LDS
 // transpose read from row-major tiles that asynchronous copies (X) and plain loads (Y) fill.
+// DUAL: Y holds two adapters' rank-space columns side by side (16 + 16); their partial results are
+// stored one after the other (rows 0..r-1 and r..2r-1 of the chunk), so X is streamed once for both.
+template <bool DUAL>
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__restrict__ X, int ldx, int C,
                                                                 const bf16 *__restrict__ Y, int ldy, int r, int T,
                                                                 float *__restrict__ partials)
 {
+    constexpr int YP = DUAL ? 96 : 32;
     __shared__ __attribute__((aligned(1024))) unsigned char X0[GX_TILE], X1[GX_TILE];
-    __shared__ __attribute__((aligned(16))) unsigned char Y0[64 * 32], Y1[64 * 32];
+    __shared__ __attribute__((aligned(16))) unsigned char Y0[64 * YP], Y1[64 * YP];
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c_blk = blockIdx.x * GR_COLS;
@@ -71,15 +79,17 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__re
     // X copy: each instruction moves 2 token rows x 512 B; lane l -> row l>>5, physical 16-byte slot
     // l&31 which holds logical slot (l&31) ^ ((row&7)<<2).  32 instructions per tile, 8 per wave.
     const int xrow = lane >> 5, xslot = lane & 31;
-    // Y copy: 128 threads x 16 B per tile, through a register (committed to LDS after the MFMA work)
+    // Y copy: 16 B per thread (128 threads for one adapter, 256 for two), through a register (committed
+    // to LDS after the MFMA work)
+    constexpr int YTHR = DUAL ? 256 : 128, YSH = DUAL ? 2 : 1, YMASK = DUAL ? 3 : 1;
     uint4 yreg = {0, 0, 0, 0};
 #define LG_ISSUE(Xs, jj)                                                                           \
     {                                                                                              \
         const int t0_ = t_begin + (jj) * 64;                                                       \
-        if (tid < 128) {                                                                           \
-            const int tr_ = t0_ + (tid >> 1);                                                      \
+        if (tid < YTHR) {                                                                          \
+            const int tr_ = t0_ + (tid >> YSH);                                                    \
             yreg = make_uint4(0, 0, 0, 0);                                                         \
-            if (tr_ < T) yreg = *(const uint4 *)(Y + (size_t)tr_ * ldy + (tid & 1) * 8);           \
+            if (tr_ < T) yreg = *(const uint4 *)(Y + (size_t)tr_ * ldy + (tid & YMASK) * 8);       \
         }                                                                                          \
         _Pragma("unroll") for (int p = 0; p < 8; ++p) {                                            \
             const int row_ = (wave * 8 + p) * 2 + xrow;                                            \
@@ -89,11 +99,11 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__re
             LG_GLDS(X + (size_t)tg_ * ldx + cg_, (Xs) + (wave * 8 + p) * 1024);                    \
         }                                                                                          \
     }
-#define LG_COMMIT(Ys) if (tid < 128) *(uint4 *)((Ys) + (tid >> 1) * 32 + (tid & 1) * 16) = yreg;
+#define LG_COMMIT(Ys) if (tid < YTHR) *(uint4 *)((Ys) + (tid >> YSH) * YP + (tid & YMASK) * 16) = yreg;
 #define LG_TILE(Xs, Ys)                                                                            \
     if (wave_ok) {                                                                                 \
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                         \
-            const bf16x8 yb = yfrag_tr(Ys, ks * 16, lane);                                         \
+            const bf16x8 yb = yfrag_tr<DUAL>(Ys, ks * 16, lane);                                   \
             _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                       \
                 acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                 \
                     xfrag_tr(Xs, wave * 64 + mt * 32, ks * 16, lane), yb, acc[mt], 0, 0, 0);       \
@@ -130,13 +140,15 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__re
 #undef LG_TILE
 
     // lane holds column j = lane%32 of D, rows c = 8(e/4) + 4g + e%4 of each 32-row tile
-    if (wave_ok && r32 < r) {
+    const int nrows = DUAL ? 2 * r : r;
+    const int jrow = (DUAL && r32 >= 16) ? r + r32 - 16 : r32;
+    if (wave_ok && (r32 & 15) < r && (DUAL || r32 < 16)) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
                 const int c = c_blk + wave * 64 + mt * 32 + 8 * e4 + 4 * g;
-                *(float4 *)(partials + ((size_t)chunk * r + r32) * C + c) =
+                *(float4 *)(partials + ((size_t)chunk * nrows + jrow) * C + c) =
                     make_float4(acc[mt][4 * e4], acc[mt][4 * e4 + 1], acc[mt][4 * e4 + 2], acc[mt][4 * e4 + 3]);
             }
     }
@@ -144,20 +156,23 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__re
 
 // out[j, c] = sum over chunks, in a fixed order: each of the 4 wavefronts of a block sums a
 // contiguous quarter of the chunks in increasing order, then the four are added in order.
+// With a second output, rows r..2r-1 of every chunk belong to it (two adapters reduced in one launch).
 __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float *__restrict__ partials, int nchunk, int r,
-                                                               int C, float *__restrict__ out, int out_is_rxC)
+                                                               int C, float *__restrict__ out,
+                                                               float *__restrict__ out_second, int out_is_rxC)
 {
     __shared__ float red[3][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int idx = blockIdx.x * 64 + lane;              // over r*C, c fastest
-    const bool ok = idx < r * C;
+    const int nrows = out_second ? 2 * r : r;
+    const int idx = blockIdx.x * 64 + lane;              // over nrows*C, c fastest
+    const bool ok = idx < nrows * C;
     const int j = ok ? idx / C : 0, c = ok ? idx - j * C : 0;
     const int per = (nchunk + 3) >> 2;
     const int k0 = wave * per, k1 = min(k0 + per, nchunk);
     float s = 0.f;
     if (ok) {
         const float *src = partials + (size_t)j * C + c;
-        const size_t step = (size_t)r * C;
+        const size_t step = (size_t)nrows * C;
         int k = k0;
         // eight loads in flight, added in increasing chunk order
         for (; k + 8 <= k1; k += 8) {
@@ -175,8 +190,10 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float *__re
         s += red[0][lane];
         s += red[1][lane];
         s += red[2][lane];
-        if (out_is_rxC) out[(size_t)j * C + c] = s;
-        else out[(size_t)c * r + j] = s;
+        float *dst = j < r ? out : out_second;
+        const int jj = j < r ? j : j - r;
+        if (out_is_rxC) dst[(size_t)jj * C + c] = s;
+        else dst[(size_t)c * r + jj] = s;
     }
 }
 
@@ -302,7 +319,7 @@ __global__ __launch_bounds__(256) void fedavg_kernel(FedTable t, size_t n, float
 size_t lora_grad_partial_floats(int T, int C)
 {
     const size_t nchunk = (size_t)(T + GR_ROWS - 1) / GR_ROWS;
-    return nchunk * SL_RP * (size_t)C;
+    return nchunk * 2 * SL_RP * (size_t)C;               // room for two adapters reduced together
 }
 
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
@@ -311,10 +328,26 @@ int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int 
     if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || r < 1 || r > 16) return -1;
     const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
     dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
-    hipLaunchKernelGGL(lora_grad_partial_kernel, grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
+    hipLaunchKernelGGL((lora_grad_partial_kernel<false>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
     SL_CHECK_LAUNCH("lora_grad_partial");
     hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
-                       out, out_is_rxC);
+                       out, (float *)nullptr, out_is_rxC);
+    SL_CHECK_LAUNCH("lora_grad_reduce");
+    return 0;
+}
+
+// Two adapters that share X: Y carries their rank-space columns in [0,16) and [16,32) of each row.
+int launch_lora_grad_pair(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
+                          float *out_a, float *out_b, int out_is_rxC, hipStream_t st)
+{
+    if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || ldy < 32 || r < 1 || r > 16 || !out_a || !out_b)
+        return -1;
+    const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
+    dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
+    hipLaunchKernelGGL((lora_grad_partial_kernel<true>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
+    SL_CHECK_LAUNCH("lora_grad_partial");
+    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((2 * r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
+                       out_a, out_b, out_is_rxC);
     SL_CHECK_LAUNCH("lora_grad_reduce");
     return 0;
 }
