@@ -359,12 +359,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
                     const int ql = 32 * st + 8 * e4 + 4 * g;                                           \
                     const f32x4 ls = *(const f32x4 *)((stt) + ql);                                     \
                     const f32x4 dd = *(const f32x4 *)((stt) + 64 + ql);                                \
-                    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                    \
-                        const int e = 4 * e4 + i;                                                      \
-                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i]));           \
-                        if (need_mask && key > (q0) + ql + i) p = 0.f;                                 \
-                        sacc[e] = p;                                                                   \
-                        dpacc[e] = p * (dpacc[e] - dd[i]);                                             \
+                    if (need_mask) {                     /* sub-tiles that touch the diagonal */       \
+                        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                \
+                            const int e = 4 * e4 + i;                                                  \
+                            float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i]));       \
+                            if (key > (q0) + ql + i) p = 0.f;                                          \
+                            sacc[e] = p;                                                               \
+                            dpacc[e] = p * (dpacc[e] - dd[i]);                                         \
+                        }                                                                              \
+                    } else {                                                                           \
+                        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                \
+                            const int e = 4 * e4 + i;                                                  \
+                            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i])); \
+                            sacc[e] = p;                                                               \
+                            dpacc[e] = p * (dpacc[e] - dd[i]);                                         \
+                        }                                                                              \
                     }                                                                                  \
                 }                                                                                      \
                 _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                     \
