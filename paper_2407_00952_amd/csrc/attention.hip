@@ -446,6 +446,203 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Fused backward for sequences of at most 512 tokens: one block of 8 wavefronts per (sequence, head)
+// produces dQ, dK and dV in one pass, so the scores, the probabilities and dP are formed once instead
+// of once per kernel, and K, V, Q, dO are read from memory once.
+//   * K of the whole sequence sits in LDS; every wave owns two 32-key blocks (w and nb-1-w, which
+//     balances the causal triangle), keeps their V fragments and their dK, dV accumulators in
+//     registers, and walks the 32-query tiles that can see them (phase 1, as in the dK/dV kernel).
+//   * dS of a query tile is written to LDS as dS^T [key][32 queries] bf16; after one barrier the 8
+//     waves each form one 16 x 16 piece of dQ = dS K over all visible keys (phase 2), in a fixed
+//     order -- no floating-point atomics, results stay bit-reproducible.
+//   * Q / dO tiles (4 KB each) are double buffered asynchronous copies, dS^T is double buffered too,
+//     so there is one barrier per query tile: phase 2 of tile i runs next to phase 1 of tile i + 1.
+constexpr int FB_MAXS = 512;
+
+// XOR mask of the 8-byte slots of a dS^T row (64 bytes = 32 queries): conflict-free both for the
+// phase-1 stores (16 lanes = 16 consecutive keys, one slot) and for the phase-2 transpose reads
+// (16 lanes = 4 consecutive keys x 4 slots)
+__device__ __forceinline__ int dsm(int key) { return (((key >> 1) & 1) << 2) | ((key >> 2) & 3); }
+
+__global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ o,
+                                                             const bf16 *__restrict__ o_lo,
+                                                             const bf16 *__restrict__ dout,
+                                                             const float *__restrict__ lse, bf16 *__restrict__ dqkv,
+                                                             int S, int H)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char Ks[FB_MAXS * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char dS0[FB_MAXS * 64], dS1[FB_MAXS * 64];
+    __shared__ __attribute__((aligned(1024))) unsigned char Qb0[32 * 128], Db0[32 * 128], Qb1[32 * 128], Db1[32 * 128];
+    __shared__ __align__(16) float lse_s[FB_MAXS], dl_s[FB_MAXS];
+    const int a = blockIdx.x, n = blockIdx.y;
+    const int d = H * 64, ld = 3 * d;
+    const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int i16 = lane & 15, kg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
+    const bf16 *dbase = dout + (size_t)n * S * d + a * 64;
+    const int nb = S >> 5;                               // 32-row blocks (even: S is a multiple of 64)
+
+    // ---- prologue: K -> LDS, per-row statistics, this wave's V fragments, first query tile
+    {
+        const int lrow = lane >> 3, lch = (lane & 7) ^ swm(lane >> 3);
+        for (int pc = wave; pc < (S >> 3); pc += 8)      // 1 KB pieces of 8 rows
+            AT_GLDS(base + d + (size_t)(pc * 8 + lrow) * ld + lch * 8, Ks + pc * 1024);
+    }
+    if (tid < S) lse_s[tid] = lse[((size_t)n * H + a) * S + tid];
+    // delta = rowsum(dO * (O + O_lo)): 8 lanes per row (16 bytes each, one full 128-byte line per row and
+    // operand), 64 rows per pass, reduced with three shuffles
+    for (int r0 = 0; r0 < S; r0 += 64) {
+        const size_t off_d = ((size_t)n * S + r0 + (tid >> 3)) * d + a * 64 + (tid & 7) * 8;
+        const bf16x8 dv = *(const bf16x8 *)(dout + off_d);
+        const bf16x8 ov = *(const bf16x8 *)(o + off_d);
+        const bf16x8 lv = *(const bf16x8 *)(o_lo + off_d);
+        float dl = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dl += bf2f(dv[i]) * (bf2f(ov[i]) + bf2f(lv[i]));
+        dl += __shfl_xor(dl, 1, 64);
+        dl += __shfl_xor(dl, 2, 64);
+        dl += __shfl_xor(dl, 4, 64);
+        if ((tid & 7) == 0) dl_s[r0 + (tid >> 3)] = dl;
+    }
+    const bool owner = wave < (nb >> 1);                 // waves beyond the number of block pairs only do phase 2
+    const int jb[2] = {wave, nb - 1 - wave};
+    bf16x8 vf[2][4];
+    f32x16 dkacc[2][2], dvacc[2][2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int key = min(32 * jb[b] + r32, S - 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            vf[b][ks] = *(const bf16x8 *)(base + 2 * d + (size_t)(owner ? key : 0) * ld + ks * 16 + g * 8);
+        dkacc[b][0] = zero16(); dkacc[b][1] = zero16(); dvacc[b][0] = zero16(); dvacc[b][1] = zero16();
+    }
+    // one 1 KB piece per wave and tile: waves 0-3 copy the Q rows, waves 4-7 the dO rows
+#define FB_COPY(Qd, Dd, it)                                                                            \
+    {                                                                                                  \
+        const int lrow_c = lane >> 3, lch_c = (lane & 7) ^ swm(lane >> 3);                             \
+        const int row_c = 32 * (it) + (wave & 3) * 8 + lrow_c;                                         \
+        if (wave < 4) AT_GLDS(base + (size_t)row_c * ld + lch_c * 8, (Qd) + (wave & 3) * 1024);        \
+        else AT_GLDS(dbase + (size_t)row_c * d + lch_c * 8, (Dd) + (wave & 3) * 1024);                 \
+    }
+    // phase 1 for query tile `it` (rows 32 it ..) against this wave's blocks that it can see
+#define FB_PHASE1(Qs, Ds, dSw, it)                                                                     \
+    if (owner) {                                                                                       \
+        _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                \
+            const int j = jb[b];                                                                       \
+            if (j <= (it)) {                                                                           \
+                const bool diag = j == (it);                                                           \
+                f32x16 sacc = zero16(), dpacc = zero16();                                              \
+                _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                     \
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Qs, r32, ks, g),            \
+                                                                    frag_rm(Ks, 32 * j + r32, ks, g), sacc, 0, 0, 0); \
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ds, r32, ks, g), vf[b][ks], \
+                                                                     dpacc, 0, 0, 0);                  \
+                }                                                                                      \
+                _Pragma("unroll") for (int e4 = 0; e4 < 4; ++e4) {                                     \
+                    const int ql = 8 * e4 + 4 * g;                                                     \
+                    const f32x4 ls = *(const f32x4 *)(lse_s + 32 * (it) + ql);                         \
+                    const f32x4 dd = *(const f32x4 *)(dl_s + 32 * (it) + ql);                          \
+                    bf16x4 dst4;                                                                       \
+                    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                    \
+                        const int e = 4 * e4 + i;                                                      \
+                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i]));           \
+                        if (diag && r32 > ql + i) p = 0.f;                                             \
+                        sacc[e] = p;                                                                   \
+                        dpacc[e] = p * (dpacc[e] - dd[i]);                                             \
+                        dst4[i] = f2bf(dpacc[e]);                                                      \
+                    }                                                                                  \
+                    const int key = 32 * j + r32;                                                      \
+                    *(bf16x4 *)((dSw) + key * 64 + (((2 * e4 + g) ^ dsm(key)) << 3)) = dst4;           \
+                }                                                                                      \
+                _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                     \
+                    bf16x8 pb, dsb;                                                                    \
+                    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                    \
+                        pb[i] = f2bf(sacc[8 * hh + i]);                                                \
+                        dsb[i] = f2bf(dpacc[8 * hh + i]);                                              \
+                    }                                                                                  \
+                    _Pragma("unroll") for (int dt = 0; dt < 2; ++dt) {                                 \
+                        dvacc[b][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
+                            frag_tr(Ds, 32 * dt, 16 * hh, lane), pb, dvacc[b][dt], 0, 0, 0);           \
+                        dkacc[b][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
+                            frag_tr(Qs, 32 * dt, 16 * hh, lane), dsb, dkacc[b][dt], 0, 0, 0);          \
+                    }                                                                                  \
+                }                                                                                      \
+            }                                                                                          \
+            __builtin_amdgcn_sched_barrier(0);           /* keep the two blocks' live ranges apart */   \
+        }                                                                                              \
+    }
+    // phase 2 for query tile `it`: wave w forms dQ[16 qt .. +15][16 dt .. +15], qt = w / 4, dt = w % 4,
+    // as (K^T dS^T)^T over all visible keys; the lane ends up with 4 consecutive columns of one query
+#define FB_PHASE2(dSr, it)                                                                             \
+    {                                                                                                  \
+        const int qt = wave >> 2, dt = wave & 3;                                                       \
+        f32x4 qacc = {0.f, 0.f, 0.f, 0.f};                                                             \
+        _Pragma("unroll 2") for (int kk = 0; kk <= (it); ++kk) {                                       \
+            union { v4s s[2]; bf16x8 v; } ua, ub;                                                      \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                            \
+                const int row = 32 * kk + 8 * kg + 4 * h + (i16 >> 2);                                 \
+                const int colk = 16 * dt + 4 * (i16 & 3);                                              \
+                const unsigned char *pk = Ks + row * 128 + (((colk >> 3) ^ swm(row)) << 4) + (colk & 7) * 2; \
+                const unsigned char *pd = (dSr) + row * 64 + (((4 * qt + (i16 & 3)) ^ dsm(row)) << 3); \
+                ua.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)pk); \
+                ub.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)pd); \
+            }                                                                                          \
+            qacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua.v, ub.v, qacc, 0, 0, 0);                 \
+        }                                                                                              \
+        const int q = 32 * (it) + 16 * qt + i16;                                                       \
+        bf16x4 w4;                                                                                     \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) w4[e] = f2bf(qacc[e] * 0.125f);                  \
+        *(bf16x4 *)(dqkv + ((size_t)n * S + q) * ld + a * 64 + 16 * dt + 4 * kg) = w4;                 \
+    }
+
+    FB_COPY(Qb0, Db0, 0)
+    AT_WAIT_VM0();
+    __syncthreads();                                     // K, statistics of tile 0 and tile 0 are in LDS
+    if (nb > 1) FB_COPY(Qb1, Db1, 1)
+    FB_PHASE1(Qb0, Db0, dS0, 0)
+    for (int it = 0; it < nb; it += 2) {
+        AT_WAIT_VM0();
+        __syncthreads();                                 // dS^T of tile it complete; tile it + 1 and its delta landed
+        if (it + 2 < nb) FB_COPY(Qb0, Db0, it + 2)
+        FB_PHASE2(dS0, it)
+        if (it + 1 < nb) FB_PHASE1(Qb1, Db1, dS1, it + 1)
+        if (it + 1 < nb) {
+            AT_WAIT_VM0();
+            __syncthreads();
+            if (it + 3 < nb) FB_COPY(Qb1, Db1, it + 3)
+            FB_PHASE2(dS1, it + 1)
+            if (it + 2 < nb) FB_PHASE1(Qb0, Db0, dS0, it + 2)
+        }
+    }
+#undef FB_COPY
+#undef FB_PHASE1
+#undef FB_PHASE2
+
+    if (owner) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int key = 32 * jb[b] + r32;
+            bf16 *krow = dqkv + ((size_t)n * S + key) * ld + d + a * 64;
+            bf16 *vrow = krow + d;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    bf16x4 wk, wv;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        wk[i] = f2bf(dkacc[b][dt][4 * e4 + i] * 0.125f);
+                        wv[i] = f2bf(dvacc[b][dt][4 * e4 + i]);
+                    }
+                    *(bf16x4 *)(krow + 32 * dt + 8 * e4 + 4 * g) = wk;
+                    *(bf16x4 *)(vrow + 32 * dt + 8 * e4 + 4 * g) = wv;
+                }
+        }
+    }
+}
+
 }  // namespace
 
 int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st)
@@ -461,6 +658,11 @@ int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16
                     float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st)
 {
     if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return -1;
+    if (S <= FB_MAXS) {
+        hipLaunchKernelGGL(attn_bwd_fused_kernel, dim3(H, n_seq), dim3(512), 0, st, qkv, o, o_lo, dout, lse, dqkv, S, H);
+        SL_CHECK_LAUNCH("attn_bwd_fused");
+        return 0;
+    }
     dim3 grid((S + 127) / 128, H, n_seq);
     hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, dout, lse, delta, dqkv, S, H);
     SL_CHECK_LAUNCH("attn_bwd_dq");
