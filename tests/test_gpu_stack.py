@@ -32,6 +32,14 @@ SMALL = {
     "narrowest-d64": synth.tiny_config(d_model=64, n_head=1, d_ff=64, n_blocks=2, lora_r=4,
                                        lora_proj=("q", "o", "pr"), n_clients=2, batch=1, seq_len=64,
                                        seed=synth.BASE_SEED + 108),
+    # sequence lengths that exercise the fused attention backward with an odd number of block pairs,
+    # and one beyond its limit of 512 (split dQ / dK,dV kernels)
+    "seq320": synth.tiny_config(d_model=128, n_head=2, d_ff=128, n_blocks=1, lora_r=4, lora_proj=("q", "k", "v"),
+                                n_clients=1, batch=2, seq_len=320, seed=synth.BASE_SEED + 109),
+    "seq448": synth.tiny_config(d_model=64, n_head=1, d_ff=64, n_blocks=1, lora_r=4, lora_proj=("q", "v"),
+                                n_clients=2, batch=1, seq_len=448, seed=synth.BASE_SEED + 110),
+    "seq576": synth.tiny_config(d_model=64, n_head=1, d_ff=64, n_blocks=1, lora_r=4, lora_proj=("q", "v"),
+                                n_clients=1, batch=2, seq_len=576, seed=synth.BASE_SEED + 111),
     # the paper sweeps the rank over {1, 2, 4, 8} (Sec. IV): r = 2 and r = 8 on the paper's (q, v) placement
     "rank2-qv": synth.tiny_config(d_model=128, n_head=2, d_ff=256, n_blocks=2, lora_r=2, lora_proj=("q", "v"),
                                   n_clients=2, batch=1, seq_len=128, seed=synth.BASE_SEED + 105),
