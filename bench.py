@@ -154,6 +154,26 @@ def main():
     gemm_ms, gemm_flop, launches = B.slora_prof_read()
     B.slora_prof_enable(0)
 
+    # the four calls of the step on their own (after the timed region, outside the GEMM statistics)
+    phases = None
+    if not args.no_legs:
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            t_ = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t_) / reps * 1e3
+
+        phases = {"fwd_ms": timed(lambda: srv.fwd(xs, y, stream))}
+        phases["fwd_bwd_ms"] = timed(lambda: (srv.fwd(xs, y, stream), srv.bwd(dy, dxs, stream)))
+        phases["bwd_ms"] = phases["fwd_bwd_ms"] - phases["fwd_ms"]
+        phases["fwd_bwd_step_ms"] = timed(lambda: (srv.fwd(xs, y, stream), srv.bwd(dy, dxs, stream), srv.step(lr, stream)))
+        phases["adapter_step_ms"] = phases["fwd_bwd_step_ms"] - phases["fwd_bwd_ms"]
+        phases["fedavg_ms"] = timed(lambda: B.slora_fedavg(fed_dev, fed_counts, n_fed, fed_out, stream), reps=20)
+        phases["fedavg_bytes"] = 4 * n_fed * (cfg.n_clients + 1)
+
     # the loss head on its own (outside the timed region and outside the GEMM statistics above)
     legs = not args.no_legs
     lh_ms = cl_ms = float("nan")
@@ -229,6 +249,8 @@ def main():
                      "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
                      "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
     }
+    if phases is not None:
+        out["phases"] = phases
     if legs:
         out["client_side"] = {"ms": cl_ms, "client_blocks": n_cb, "tokens": cfg.batch * cfg.seq_len,
                               "tokens_per_s": cfg.batch * cfg.seq_len / (cl_ms * 1e-3),
