@@ -1,0 +1,112 @@
+"""Plain CPU oracle for the compressed (microscaling fp8) frozen linear and cut-layer traffic.
+
+THIS IS TEST INFRASTRUCTURE (see slora_oracle.py): slow, plain, independent of the
+HIP path, never imported by the product package.
+
+What it follows.  SplitLoRA (arXiv 2407.00952) names quantisation of the model as the way
+to a more storage-, communication- and computation-efficient framework (Sec. V-B) and
+fixes no format.  The format taken here is the published OCP Microscaling (MX) v1.0
+"MXFP8" one: a block of 32 consecutive elements along the contraction axis shares one
+power-of-two scale (E8M0: an 8-bit biased exponent, value 2^(code-127), code 255 = NaN),
+elements are FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
+infinities; S.1111.111 = NaN; largest finite value 448; subnormals m * 2^-9).
+
+Conversion of a block V_1..V_32 (MX v1.0, Sec. 6.3):
+    shared_exp = floor(log2(max_i |V_i|)) - emax_elem,     emax_elem = 8 for E4M3
+    X = 2^shared_exp  (clamped to what E8M0 can hold)
+    P_i = V_i / X rounded to the nearest E4M3 value, ties to even, values beyond the
+          largest normal clamped to it
+Readings where the specification leaves a choice:
+  * a block whose largest magnitude is zero or below 2^-119 gets the smallest scale
+    (code 0): with E the biased binary32 exponent of the maximum, the rule is code = max(E - 8, 0);
+  * inputs are finite (bf16 activations and weights); NaN/Inf are not supported.
+The scale is a power of two, so V_i / X is exact: every decision below is exact integer or
+exact binary arithmetic and does not depend on the working precision.
+
+The linear layer is then the plain definition on the dequantised values, in float64:
+    y = deq(x) . deq(W)^T + bias
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BLOCK = 32
+E4M3_MAX = 448.0
+
+
+def _e4m3_table():
+    """value of each of the 256 codes, from the format definition (NaN for S.1111.111)"""
+    t = np.empty(256, dtype=np.float64)
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            v = np.nan
+        elif e == 0:
+            v = m * 2.0 ** -9                       # subnormal: 0.m * 2^(1-7)
+        else:
+            v = (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        t[c] = -v if s else v
+    return t
+
+
+E4M3 = _e4m3_table()
+# the 127 non-negative finite values in increasing order: code c (0..126) <-> value E4M3[c]
+_POS = E4M3[:127].copy()
+
+
+def e4m3_decode(codes):
+    return E4M3[np.asarray(codes, dtype=np.uint8)]
+
+
+def e4m3_encode(v):
+    """nearest E4M3 code of each value: ties to the even code, saturating at +-448, sign of zero kept"""
+    v = np.asarray(v, dtype=np.float64)
+    a = np.abs(v)
+    a = np.minimum(a, E4M3_MAX)
+    hi = np.searchsorted(_POS, a, side="left")              # first value >= a
+    hi = np.minimum(hi, 126)
+    lo = np.maximum(hi - 1, 0)
+    dlo, dhi = a - _POS[lo], _POS[hi] - a
+    # consecutive codes are consecutive values, so "even mantissa" is "even code"
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    code = np.where(np.signbit(v), code | 0x80, code).astype(np.uint8)
+    return np.where(np.isnan(v), np.uint8(0x7F), code).astype(np.uint8)
+
+
+def e8m0_decode(codes):
+    return np.ldexp(1.0, np.asarray(codes, dtype=np.int64) - 127)
+
+
+def mx_quantize(x):
+    """x [..., K] (K a multiple of 32) -> (codes uint8 [..., K], scales uint8 [..., K/32])"""
+    x = np.asarray(x, dtype=np.float64)
+    K = x.shape[-1]
+    if K % BLOCK:
+        raise ValueError("K must be a multiple of 32")
+    if not np.isfinite(x).all():
+        raise ValueError("non-finite input")
+    xb = x.reshape(x.shape[:-1] + (K // BLOCK, BLOCK))
+    amax = np.abs(xb).max(axis=-1)
+    # floor(log2 amax) from the binary exponent (amax = m 2^e, m in [0.5, 1)); code = biased exponent - 8,
+    # held at the ends of what E8M0 stores (code 0 also for the zero block)
+    _, e = np.frexp(amax)
+    scode = np.where(amax > 0, np.clip(e.astype(np.int64) - 1 + 127 - 8, 0, 254), 0)
+    scaled = np.ldexp(xb, (127 - scode)[..., None])          # exact: division by a power of two
+    codes = e4m3_encode(scaled).reshape(x.shape)
+    return codes, scode.astype(np.uint8)
+
+
+def mx_dequantize(codes, scales):
+    codes = np.asarray(codes, dtype=np.uint8)
+    K = codes.shape[-1]
+    v = e4m3_decode(codes).reshape(codes.shape[:-1] + (K // BLOCK, BLOCK))
+    return (v * e8m0_decode(scales)[..., None]).reshape(codes.shape)
+
+
+def mx_linear(xq, xs, wq, ws, bias=None):
+    """y [M,N] = deq(x)[M,K] . deq(W)[N,K]^T + bias, float64"""
+    y = mx_dequantize(xq, xs) @ mx_dequantize(wq, ws).T
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y

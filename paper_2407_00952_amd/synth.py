@@ -223,3 +223,22 @@ def make_loss_head_inputs(n_seq, seq_len, d_model, vocab=GPT2_VOCAB, seed=BASE_S
         labels[s, :c] = -1
     out["labels"] = labels.reshape(-1)
     return out
+
+
+def make_mx_linear_inputs(M, K, N, seed=BASE_SEED + 4 + 3000, outliers=True):
+    """Inputs of one frozen linear layer in compressed form, all bf16-representable.
+
+    Returns dict(x [M,K], W [N,K], bias [N]).  x has the look of a LayerNorm output (unit normal) with,
+    when `outliers`, a handful of feature columns 8..30 times larger (the channel outliers of transformer
+    activations, which is what a per-block scale is for) and one all-zero block per 61 rows; W ~ N(0, 0.02^2)
+    as in GPT-2's initialisation; bias ~ N(0, 0.02^2).  Draw order: x, column factors, W, bias.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = _normal(rng, (M, K), 1.0)
+    if outliers:
+        cols = rng.choice(K, size=max(K // 128, 1), replace=False)
+        x[:, cols] *= rng.uniform(8.0, 30.0, size=len(cols)).astype(x.dtype)
+        x[::61, :32] = 0.0
+    W = _normal(rng, (N, K), 0.02)
+    bias = _normal(rng, (N,), 0.02)
+    return dict(x=round_bf16(x), W=round_bf16(W), bias=round_bf16(bias))

@@ -1,0 +1,165 @@
+"""Pins for oracle/mx.py (MXFP8 conversion and the quantised linear).
+
+What fixes the oracle here: the format constants and hand-worked blocks of the OCP MX v1.0
+specification (tests/golden/mx_examples.txt), torch's own float8_e4m3fn cast as an independent
+round-to-nearest-even implementation, a brute-force nearest-value search over all codes, and
+properties that follow from the definition (scale window, idempotence, exactness on representable
+data, reduction of the linear layer to a plain matmul)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mx
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "mx_examples.txt")
+
+
+def _gold():
+    e4, e8, blocks = [], [], []
+    for line in open(GOLD):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        kind, rest = line.split(None, 1)
+        if kind == "E4M3":
+            c, v = rest.split()
+            e4.append((int(c, 16), float(v)))
+        elif kind == "E8M0":
+            c, v = rest.split()
+            e8.append((int(c), int(v)))
+        else:
+            vals, sc, codes = [p.strip() for p in rest.split("|")]
+            blocks.append(([float(t) for t in vals.split()], int(sc), [int(t, 16) for t in codes.split()]))
+    return e4, e8, blocks
+
+
+def test_format_constants_from_the_specification():
+    e4, e8, _ = _gold()
+    for c, v in e4:
+        assert mx.e4m3_decode(np.uint8(c)) == v
+    for c, lg in e8:
+        assert mx.e8m0_decode(c) == 2.0 ** lg
+    assert np.isnan(mx.e4m3_decode(np.uint8(0x7F))) and np.isnan(mx.e4m3_decode(np.uint8(0xFF)))
+    assert np.signbit(mx.e4m3_decode(np.uint8(0x80))) and mx.e4m3_decode(np.uint8(0x80)) == 0.0
+    # monotone over the positive codes, 126 distinct positive finite values
+    pos = mx.e4m3_decode(np.arange(127, dtype=np.uint8))
+    assert (np.diff(pos) > 0).all()
+
+
+def test_hand_worked_blocks():
+    _, _, blocks = _gold()
+    for vals, sc, codes in blocks:
+        x = np.zeros(32)
+        x[:len(vals)] = vals
+        q, s = mx.mx_quantize(x[None, :])
+        assert int(s[0, 0]) == sc, (vals, s)
+        want = np.zeros(32, dtype=np.uint8)
+        want[:len(codes)] = codes
+        np.testing.assert_array_equal(q[0], want)
+
+
+def test_encode_inverts_decode_on_every_finite_code():
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    np.testing.assert_array_equal(mx.e4m3_encode(mx.e4m3_decode(codes)), codes)
+
+
+def test_encode_matches_torch_float8_cast_in_range():
+    rng = np.random.default_rng(0)
+    v = np.concatenate([
+        rng.uniform(-448, 448, 20000), rng.normal(0, 1, 20000), rng.normal(0, 0.01, 20000),
+        # every midpoint between neighbouring values (the ties) and points just beside them
+        (mx._POS[1:] + mx._POS[:-1]) / 2, -(mx._POS[1:] + mx._POS[:-1]) / 2,
+        np.nextafter((mx._POS[1:] + mx._POS[:-1]) / 2, 1e9), np.nextafter((mx._POS[1:] + mx._POS[:-1]) / 2, -1e9),
+    ]).astype(np.float32)
+    ref = torch.from_numpy(v).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = mx.e4m3_encode(v.astype(np.float64))
+    np.testing.assert_array_equal(got, ref)
+
+
+def test_encode_is_the_nearest_value_with_ties_to_even_and_saturation():
+    rng = np.random.default_rng(1)
+    v = np.concatenate([rng.uniform(-520, 520, 3000), rng.normal(0, 0.02, 3000)])
+    finite = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    table = mx.e4m3_decode(finite)
+    got = mx.e4m3_encode(v)
+    for x, c in zip(v, got):
+        d = np.abs(table - x)
+        best = d.min()
+        assert abs(mx.e4m3_decode(c) - x) == best
+        cands = finite[d == best]
+        if len(cands) > 1 and x != 0:           # a tie: the even code wins
+            assert c % 2 == 0
+    # beyond the largest normal: clamp, never NaN
+    np.testing.assert_array_equal(mx.e4m3_encode(np.array([449.0, 464.0, 480.0, 511.9, -1e6])),
+                                  np.array([0x7E, 0x7E, 0x7E, 0x7E, 0xFE], dtype=np.uint8))
+
+
+def test_block_scale_window_and_error_bound():
+    rng = np.random.default_rng(2)
+    x = (rng.normal(0, 1, (64, 256)) * 10.0 ** rng.uniform(-6, 6, (64, 1))).astype(np.float32).astype(np.float64)
+    q, s = mx.mx_quantize(x)
+    X = mx.e8m0_decode(s)
+    amax = np.abs(x.reshape(64, 8, 32)).max(axis=-1)
+    # shared_exp = floor(log2 amax) - 8  <=>  amax / X in [256, 512)
+    assert ((amax / X >= 256) & (amax / X < 512)).all()
+    d = mx.mx_dequantize(q, s)
+    err = np.abs(d - x).reshape(64, 8, 32)
+    # elements below 448 X are rounded to nearest: half a spacing, spacing <= 2^-3 of the value's binade
+    # (or 2^-9 X for subnormals); elements in (448 X, 512 X) are clamped: error < 64 X
+    bound = np.maximum(np.abs(x).reshape(64, 8, 32) * 2.0 ** -4, X[..., None] * 2.0 ** -10)
+    clamped = np.abs(x).reshape(64, 8, 32) > 448 * X[..., None]
+    assert (err[~clamped] <= bound[~clamped]).all()
+    assert (err[clamped] < 64 * np.broadcast_to(X[..., None], err.shape)[clamped]).all()
+
+
+def test_quantise_is_idempotent_and_exact_on_representable_data():
+    rng = np.random.default_rng(3)
+    x = rng.normal(0, 3, (16, 128))
+    q, s = mx.mx_quantize(x)
+    d = mx.mx_dequantize(q, s)
+    q2, s2 = mx.mx_quantize(d)
+    np.testing.assert_array_equal(q2, q)
+    np.testing.assert_array_equal(s2, s)
+    # data that is already an E4M3 value times a power of two per block survives unchanged
+    codes = rng.integers(0, 127, (16, 128)).astype(np.uint8)
+    codes[:, ::32] = 0x7E                          # pin every block's maximum to 448
+    sc = rng.integers(100, 150, (16, 4)).astype(np.uint8)
+    y = mx.mx_dequantize(codes, sc)
+    qy, sy = mx.mx_quantize(y)
+    np.testing.assert_array_equal(qy, codes)
+    np.testing.assert_array_equal(sy, sc)
+
+
+def test_linear_reduces_to_a_plain_matmul():
+    rng = np.random.default_rng(4)
+    M, K, N = 5, 64, 7
+    xq = rng.integers(0, 127, (M, K)).astype(np.uint8) | (rng.integers(0, 2, (M, K)).astype(np.uint8) << 7)
+    wq = rng.integers(0, 127, (N, K)).astype(np.uint8) | (rng.integers(0, 2, (N, K)).astype(np.uint8) << 7)
+    xs = rng.integers(120, 134, (M, K // 32)).astype(np.uint8)
+    ws = rng.integers(120, 134, (N, K // 32)).astype(np.uint8)
+    b = rng.normal(0, 1, N)
+    y = mx.mx_linear(xq, xs, wq, ws, b)
+    # the same by explicit loops over blocks and elements
+    ref = np.zeros((M, N))
+    for m in range(M):
+        for n in range(N):
+            acc = 0.0
+            for kb in range(K // 32):
+                sx, sw = 2.0 ** (int(xs[m, kb]) - 127), 2.0 ** (int(ws[n, kb]) - 127)
+                for k in range(32):
+                    acc += (mx.E4M3[xq[m, kb * 32 + k]] * sx) * (mx.E4M3[wq[n, kb * 32 + k]] * sw)
+            ref[m, n] = acc + b[n]
+    np.testing.assert_allclose(y, ref, rtol=1e-13, atol=1e-13)
+    # all-ones data with unit scales: every output is K
+    one = np.full((M, K), 0x38, dtype=np.uint8)
+    u = np.full((M, K // 32), 127, dtype=np.uint8)
+    np.testing.assert_array_equal(mx.mx_linear(one, u, one[:3], u[:3]), np.full((M, 3), float(K)))
+
+
+def test_rejects_bad_input():
+    with pytest.raises(ValueError):
+        mx.mx_quantize(np.zeros((2, 48)))
+    with pytest.raises(ValueError):
+        mx.mx_quantize(np.array([[np.inf] + [0.0] * 31]))
