@@ -72,6 +72,59 @@ def recorded_gemm_traffic():
     return None
 
 
+PEAK_FP8_TFLOPS = 5000.0
+
+
+def mxfp8_leg(cfg, stream):
+    """The four frozen linears of a block's forward pass in MXFP8 (fp8 matrix cores, block scales), timed one
+    by one on the workload's token count, next to the bf16 kernel on the same shapes; plus the conversion of
+    one [T, d] activation tensor.  Separate from the metric's step, which stays bf16."""
+    import torch
+    from paper_2407_00952_amd import binding as B
+    T, d, dff = cfg.tokens, cfg.d_model, cfg.d_ff
+    g = torch.Generator(device="cuda")
+    g.manual_seed(cfg.seed + 9000)
+
+    def timed(fn, reps=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t_ = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_) / reps * 1e3
+
+    shapes, flop, ms_mx, ms_bf = [], 0.0, 0.0, 0.0
+    quant = None
+    for name, K, N in (("qkv", d, 3 * d), ("o", d, d), ("fc", d, dff), ("proj", dff, d)):
+        x = torch.randn((T, K), device="cuda", generator=g).to(torch.bfloat16)
+        W = (torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        xq = torch.empty((T, K), dtype=torch.uint8, device="cuda")
+        xs = torch.empty((T, K // 32), dtype=torch.uint8, device="cuda")
+        wq = torch.empty((N, K), dtype=torch.uint8, device="cuda")
+        ws = torch.empty((N, K // 32), dtype=torch.uint8, device="cuda")
+        y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+        B.slora_mx_quantize(N, K, W, K, wq, ws, stream)
+        tq = timed(lambda: B.slora_mx_quantize(T, K, x, K, xq, xs, stream))
+        if name == "qkv":
+            nbytes = T * K * (2 + 1) + T * K // 32
+            quant = {"ms": tq, "bytes": nbytes, "gb_s": nbytes / (tq * 1e-3) / 1e9}
+        t_mx = timed(lambda: B.slora_frozen_linear_mxfp8(T, K, N, xq, xs, wq, ws, None, y, stream))
+        t_bf = timed(lambda: B.slora_frozen_linear_bf16(T, K, N, x, W, None, y, stream))
+        f = 2.0 * T * K * N
+        shapes.append({"name": name, "K": K, "N": N, "mxfp8_us": t_mx * 1e3, "bf16_us": t_bf * 1e3,
+                       "mxfp8_tflops": f / (t_mx * 1e-3) / 1e12})
+        flop += f
+        ms_mx += t_mx
+        ms_bf += t_bf
+        del x, W, xq, xs, wq, ws, y
+    ach = flop / (ms_mx * 1e-3) / 1e12
+    return {"what": "y = deq(x) deq(W)^T, MXFP8 operands (E4M3 + E8M0 per 32), bf16 out, T=%d" % T,
+            "shapes": shapes, "tflops": ach, "peak": PEAK_FP8_TFLOPS, "frac": ach / PEAK_FP8_TFLOPS,
+            "speedup_over_bf16_kernel": ms_bf / ms_mx, "quantize_activation": quant}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -217,6 +270,8 @@ def main():
         cl_ms = (time.perf_counter() - t2) / 10 * 1e3
         del cl
 
+    mx_leg = mxfp8_leg(cfg, stream) if legs else None
+
     if args.copy_calibration:
         n_cal = 64 * 1024 * 1024
         src = torch.ones(n_cal, dtype=torch.float32, device="cuda")
@@ -255,6 +310,7 @@ def main():
         out["client_side"] = {"ms": cl_ms, "client_blocks": n_cb, "tokens": cfg.batch * cfg.seq_len,
                               "tokens_per_s": cfg.batch * cfg.seq_len / (cl_ms * 1e-3),
                               "what": "one client: embedding + client blocks forward, backward, SGD step"}
+        out["mxfp8_linear"] = mx_leg
         out["loss_head"] = {"ms": lh_ms, "vocab": V, "tflops": lh_flop / (lh_ms * 1e-3) / 1e12,
                             "in_timed_step": bool(args.loss_head)}
     if not args.no_cpu_baseline:

@@ -186,6 +186,35 @@ int slora_loss_head(int32_t T, int32_t d_model, int32_t vocab, const void *y, co
                     const void *lnf_b, float eps, const int32_t *labels, void *ws, size_t ws_bytes,
                     float *loss_tok, float *loss, void *dy, void *stream);
 
+/* ---- compressed frozen weights and cut-layer traffic (Sec. V-B: quantisation as the route to a more
+ *      storage-, communication- and computation-efficient framework; the paper fixes no format) -------
+ * Format: MXFP8 of the OCP Microscaling Formats (MX) v1.0 specification.  A row of K elements (K a
+ * multiple of 32) becomes K element codes (FP8 E4M3, one byte each) and K/32 scale codes (E8M0, one byte
+ * per block of 32 consecutive elements, value 2^(code-127)).  Conversion (MX v1.0 Sec. 6.3):
+ * scale code = max(E - 8, 0) with E the biased binary32 exponent of the block's largest magnitude;
+ * element = value / scale rounded to nearest, ties to even, clamped at +-448; the sign of zero is kept.
+ * Inputs must be finite.  All pointers are device pointers; nothing synchronises the stream; nothing is
+ * allocated.
+ *
+ * slora_mx_quantize:   x bf16 [M, K] with row stride ldx (elements, multiple of 8, 16-byte aligned base)
+ *                      -> codes u8 [M, K] (8-byte aligned), scales u8 [M, K/32], both dense.
+ * slora_mx_dequantize: the inverse map to bf16 [M, K] with row stride ldy; exact whenever the value is in
+ *                      bf16's range (an E4M3 value has 4 significant bits).
+ * These two are also the codec for what crosses the cut (the activations of step a2 and their gradients
+ * of step a4, Sec. III-B): 8.25 bits per element instead of 16.
+ *
+ * slora_frozen_linear_mxfp8: y[T, n_out] = deq(x)[T, n_in] . deq(W)[n_out, n_in]^T + bias on the fp8 matrix
+ *                      cores (block scales applied by the hardware, fp32 accumulation, bf16 output, dense
+ *                      row-major).  n_in a multiple of 128, n_out a multiple of 8, T * n_in and
+ *                      n_out * n_in below 2^32; xq, wq, y (and bias, bf16 [n_out], may be NULL) 16-byte
+ *                      aligned, xs and ws 4-byte aligned.  NaN codes (S.1111.111) must not occur.
+ * Errors: SLORA_EINVAL for a NULL pointer, a size or alignment outside the above; SLORA_EHIP. */
+int slora_mx_quantize(int64_t M, int32_t K, const void *x, int64_t ldx, void *codes, void *scales, void *stream);
+int slora_mx_dequantize(int64_t M, int32_t K, const void *codes, const void *scales, void *y, int64_t ldy,
+                        void *stream);
+int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void *xq, const void *xs,
+                              const void *wq, const void *ws, const void *bias, void *y, void *stream);
+
 /* ---- measurement hook (not part of the method) ---------------------------------------------------- */
 /* While enabled, every launch of the bf16 GEMM kernel (the frozen products of Sec. II-C with the
  * fused low-rank branch) is bracketed by HIP events on its stream.  slora_prof_read waits for the

@@ -28,7 +28,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_lora_linear_bwd", "slora_strerror", "slora_last_hip_error", "slora_prof_enable",
            "slora_prof_read", "slora_frozen_linear_bf16", "slora_loss_head_ws_bytes",
            "slora_loss_head_prepare", "slora_loss_head", "slora_client_fwd", "slora_client_bwd",
-           "slora_adapters_changed", "slora_adamw"]
+           "slora_adapters_changed", "slora_adamw", "slora_mx_quantize", "slora_mx_dequantize",
+           "slora_frozen_linear_mxfp8"]
 
 
 class slora_config(ctypes.Structure):
@@ -79,6 +80,10 @@ def lib():
         L.slora_loss_head_ws_bytes.restype = sz
         L.slora_loss_head_prepare.argtypes = [i32, i32, vp, vp, sz, vp]
         L.slora_loss_head.argtypes = [i32, i32, i32, vp, vp, vp, f32, vp, vp, sz, vp, vp, vp, vp]
+        i64 = ctypes.c_int64
+        L.slora_mx_quantize.argtypes = [i64, i32, vp, i64, vp, vp, vp]
+        L.slora_mx_dequantize.argtypes = [i64, i32, vp, vp, vp, i64, vp]
+        L.slora_frozen_linear_mxfp8.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.slora_prof_enable.argtypes = [i32]
         L.slora_prof_read.argtypes = [vp, vp, vp]
         L.slora_strerror.argtypes = [i32]
@@ -184,6 +189,19 @@ def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, d
 
 def slora_frozen_linear_bf16(T, n_in, n_out, x, W, bias, y, stream=None):
     _check(lib().slora_frozen_linear_bf16(T, n_in, n_out, _p(x), _p(W), _p(bias), _p(y), _stream(stream)))
+
+
+def slora_mx_quantize(M, K, x, ldx, codes, scales, stream=None):
+    _check(lib().slora_mx_quantize(M, K, _p(x), ldx, _p(codes), _p(scales), _stream(stream)))
+
+
+def slora_mx_dequantize(M, K, codes, scales, y, ldy, stream=None):
+    _check(lib().slora_mx_dequantize(M, K, _p(codes), _p(scales), _p(y), ldy, _stream(stream)))
+
+
+def slora_frozen_linear_mxfp8(T, n_in, n_out, xq, xs, wq, ws, bias, y, stream=None):
+    _check(lib().slora_frozen_linear_mxfp8(T, n_in, n_out, _p(xq), _p(xs), _p(wq), _p(ws), _p(bias), _p(y),
+                                           _stream(stream)))
 
 
 def slora_client_fwd(ctx, batch, tokens, vocab, wte, wpe, act, stream=None):

@@ -1,0 +1,358 @@
+// Compressed frozen linears and cut-layer traffic in the OCP microscaling format MXFP8 (gfx950).
+//
+// SplitLoRA names quantisation as the route to a more storage-, communication- and computation-
+// efficient framework (Sec. V-B) without fixing a format.  The format here is MXFP8 of the OCP
+// Microscaling Formats (MX) v1.0 specification: blocks of 32 consecutive elements along the
+// contraction axis share one power-of-two scale (E8M0 byte, value 2^(code-127)); elements are FP8
+// E4M3 (bias 7, largest finite value 448, S.1111.111 = NaN, no infinities).  CDNA4's matrix cores
+// take exactly this: V_MFMA_SCALE_F32_16X16X128_F8F6F4 multiplies two 16 x 128 fp8 operands and
+// applies one E8M0 scale per 32-element block of each, at twice the bf16 rate.
+//
+//   mx_quantize    bf16 [M,K]  -> codes u8 [M,K] + scales u8 [M,K/32]      (MX v1.0 Sec. 6.3)
+//   mx_dequantize  codes + scales -> bf16 [M,K]                            (exact unless out of bf16 range)
+//   linear         y[M,N] = deq(x)[M,K] . deq(W)[N,K]^T + bias             bf16 out, fp32 accumulation
+//
+// Operand layout of the scaled MFMA (checked on the device against a CPU product): lane l holds row
+// l%16 of its operand; with g = l/16 its eight dwords are bytes [16g, 16g+16) and [64+16g, 64+16g+16)
+// of the row's 128-byte k-slab; the scale it supplies (byte `opsel` of the scale register) belongs to
+// block g, i.e. to bytes [32g, 32g+32) of the slab.  Output as for the bf16 shapes: column l%16,
+// rows 4g + e.
+#include "../../include/slora.h"
+#include "common.h"
+
+namespace {
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------------
+// conversion kernels
+// ------------------------------------------------------------------------------------------------
+
+// E4M3 code of a non-negative fp32 value below 512: round to nearest, ties to even, clamp at 448.
+__device__ __forceinline__ unsigned e4m3_from_f32(float a)
+{
+    a = fminf(a, 448.0f);
+    if (a < 0.015625f)                                   // below the smallest normal 2^-6: multiples of 2^-9
+        return (unsigned)__builtin_rintf(a * 512.0f);    // 8 is the code of 2^-6 itself
+    unsigned b = __float_as_uint(a);
+    b += 0x7FFFFu + ((b >> 20) & 1u);                    // ties to even on the 3 kept mantissa bits
+    return (b >> 20) - ((127u - 7u) << 3);               // rebias the exponent
+}
+
+// Each thread converts 8 consecutive elements of a row; 4 neighbouring threads form a block of 32.
+__global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict__ x, long long ldx, long long M, int K,
+                                                          unsigned char *__restrict__ codes,
+                                                          unsigned char *__restrict__ scales)
+{
+    const int cpr = K >> 3;                              // 16-byte chunks per row
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = t < M * cpr;
+    const long long row = live ? t / cpr : 0;
+    const int ch = live ? (int)(t - row * cpr) : 0;
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    if (live) raw = *(const uint4 *)(x + row * ldx + ch * 8);
+    const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+    // largest magnitude of the block, compared on the bit patterns (monotone for finite values)
+    unsigned mag = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        mag = max(mag, w[i] & 0x7FFFu);
+        mag = max(mag, (w[i] >> 16) & 0x7FFFu);
+    }
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
+    // shared exponent: floor(log2 max) - 8, i.e. scale code = biased exponent - 8, held at 0
+    const int E = (int)(mag >> 7);
+    const int scode = max(E - 8, 0);
+    unsigned out[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned h = (i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu);
+        const float v = __uint_as_float((h & 0x7FFFu) << 16);
+        const float sc = ldexpf(v, 127 - scode);         // exact: division by the block scale
+        const unsigned c = e4m3_from_f32(sc) | ((h >> 8) & 0x80u);
+        out[i >> 2] |= c << (8 * (i & 3));
+    }
+    if (live) {
+        *(uint2 *)(codes + row * (long long)K + ch * 8) = make_uint2(out[0], out[1]);
+        if ((ch & 3) == 0) scales[row * (long long)(K >> 5) + (ch >> 2)] = (unsigned char)scode;
+    }
+}
+
+__device__ __forceinline__ float e4m3_to_f32(unsigned c)
+{
+    const unsigned e = (c >> 3) & 15u, m = c & 7u;
+    const float mag = e ? __uint_as_float(((e + 120u) << 23) | (m << 20)) : (float)m * 0.001953125f;
+    return (c & 0x80u) ? -mag : mag;
+}
+
+__global__ __launch_bounds__(256) void mx_dequantize_kernel(const unsigned char *__restrict__ codes,
+                                                            const unsigned char *__restrict__ scales, long long M,
+                                                            int K, bf16 *__restrict__ y, long long ldy)
+{
+    const int cpr = K >> 3;
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= M * cpr) return;
+    const long long row = t / cpr;
+    const int ch = (int)(t - row * cpr);
+    const uint2 raw = *(const uint2 *)(codes + row * (long long)K + ch * 8);
+    const int scode = scales[row * (long long)(K >> 5) + (ch >> 2)];
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned c = ((i < 4 ? raw.x : raw.y) >> (8 * (i & 3))) & 0xFFu;
+        o[i] = f2bf(ldexpf(e4m3_to_f32(c), scode - 127));
+    }
+    *(bf16x8 *)(y + row * ldy + ch * 8) = o;
+}
+
+// ------------------------------------------------------------------------------------------------
+// GEMM: 256 x 256 x 128 block tile, 8 waves (2 x 4), wave tile 128 x 64 = 8 x 4 scaled MFMA tiles.
+// Same skeleton as the bf16 GEMM (a 128-byte LDS row is one k-slab of a tile row, two stages filled by
+// asynchronous global->LDS copies, 16-byte XOR swizzle, XCD-aware tile order, LDS-transposed epilogue);
+// a slab now spans 128 contraction elements, and each stage also carries the 4 scale bytes of every row.
+// ------------------------------------------------------------------------------------------------
+constexpr int BM = 256, BN = 256, BKB = 128, NTHR = 512;   // BKB: bytes = fp8 elements per slab row
+constexpr int XB = BM * BKB, WB = BN * BKB, SB = BM * 4;   // tile bytes; scale bytes per operand tile
+constexpr int STAGE = XB + WB + 2 * SB;
+
+struct MxArgs {
+    const unsigned char *X, *XS;     // codes [M,K], scales [M,K/32]
+    const unsigned char *W, *WS;     // codes [N,K], scales [N,K/32]
+    const bf16 *bias;                // [N] or null
+    bf16 *out;                       // [M,N]
+    int M, N, K;
+};
+
+__device__ __forceinline__ void glds16(const void *sbase, unsigned voff, unsigned lds)
+{
+    // M0 carries the LDS address; one wait state is required between its write and the copy
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void glds4(const void *sbase, unsigned voff, unsigned lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ unsigned lds_addr(const void *p)
+{
+    return (unsigned)(unsigned long long)(const __attribute__((address_space(3))) char *)p;
+}
+#define MX_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
+
+__global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int r16 = lane & 15, kg = lane >> 4;
+
+    // consecutive logical tiles go to the same XCD; inside an XCD's range panels of 4 row tiles
+    const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
+    const int nb = tiles_m * tiles_n;
+    const int per_xcd = (nb + 7) >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= nb) return;
+    constexpr int PANEL = 4;
+    const int pidx = logical / (PANEL * tiles_n), prem = logical - pidx * (PANEL * tiles_n);
+    const int prow = min(PANEL, tiles_m - pidx * PANEL);
+    const int tn = prem / prow, tm = pidx * PANEL + prem - tn * prow;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // ---- copies: per stage every wave moves 32 rows of each tile (8 rows = 1 KB per instruction, lane l
+    //      -> row l>>3, physical 16-byte chunk l&7 holding logical chunk (l&7)^(l>>3)) and 64 rows' scale
+    //      dwords of one operand (waves 0-3: X, waves 4-7: W)
+    const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
+    // per-lane byte offsets are formed at each copy (two VALU operations) instead of being held in eight
+    // registers through the loop: the accumulators and fragments leave none to spare, and a spilled
+    // offset would put a scratch reload, and with it a wait for every copy in flight, between the copies
+    const int xrow0 = m0 + wave * 32 + lrow, wrow0 = n0 + wave * 32 + lrow;
+    const unsigned lch16 = lch * 16;
+    const int kb4 = a.K >> 5;                            // scale bytes per row
+    const bool sx = wave < 4;
+    const int srow = sx ? min(m0 + wave * 64 + lane, a.M - 1) : min(n0 + (wave - 4) * 64 + lane, a.N - 1);
+    const unsigned so = (unsigned)srow * (unsigned)kb4;
+    const unsigned char *Sb = sx ? a.XS : a.WS;
+    const int s_lds = XB + WB + (sx ? 0 : SB) + (wave & 3) * 256;
+    const int wofs = wave * 32 * BKB;
+
+    f32x4 acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
+
+    const int a_row = (wm * 128 + r16) * BKB, b_row = (wn * 64 + r16) * BKB;
+    const int sw = r16 & 7;
+    const int c0 = ((kg ^ sw) << 4), c1 = (((4 + kg) ^ sw) << 4);      // the lane's two 16-byte chunks
+    const int as_off = XB + WB + (wm * 128 + r16) * 4 + kg, bs_off = XB + WB + SB + (wn * 64 + r16) * 4 + kg;
+
+#define MX_ISSUE(st, kt, p)                                                               \
+    {                                                                                     \
+        int xr_ = xrow0, wr_ = wrow0;                                                     \
+        asm volatile("" : "+v"(xr_), "+v"(wr_));                                          \
+        const unsigned xo_ = (unsigned)min(xr_ + (p) * 8, a.M - 1) * (unsigned)a.K + lch16; \
+        const unsigned wo_ = (unsigned)min(wr_ + (p) * 8, a.N - 1) * (unsigned)a.K + lch16; \
+        glds16(a.X + (size_t)(kt) * BKB, xo_, lds_addr(st) + wofs + (p) * 1024);          \
+        glds16(a.W + (size_t)(kt) * BKB, wo_, lds_addr(st) + XB + wofs + (p) * 1024);     \
+        if ((p) == 0) glds4(Sb + (size_t)(kt) * 4, so, lds_addr(st) + s_lds);             \
+    }
+#define MX_FRAG(dst, base, off)                                                           \
+    {                                                                                     \
+        (dst).lo = *(const i32x4 *)((base) + (off) + c0);                                 \
+        (dst).hi = *(const i32x4 *)((base) + (off) + c1);                                 \
+    }
+    // one slab: the W fragments and scales once, the X fragments two row tiles at a time (the accumulators
+    // take half of the register file, so only a quarter of the X operand is held at once)
+#define MX_STEP(st)                                                                       \
+    {                                                                                     \
+        const unsigned char *S_ = (st);                                                   \
+        i32x8 bfr[4];                                                                     \
+        int bsc[4];                                                                       \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                   \
+            MX_FRAG(bfr[j], S_ + XB, b_row + j * 16 * BKB)                                \
+            bsc[j] = S_[bs_off + j * 64];                                                 \
+        }                                                                                 \
+        _Pragma("unroll") for (int iq = 0; iq < 4; ++iq) {                                \
+            i32x8 af[2];                                                                  \
+            int asc[2];                                                                   \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i) {                               \
+                MX_FRAG(af[i], S_, a_row + (iq * 2 + i) * 16 * BKB)                       \
+                asc[i] = S_[as_off + (iq * 2 + i) * 64];                                  \
+            }                                                                             \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i)                                 \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                             \
+                    acc[iq * 2 + i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4( \
+                        af[i], bfr[j], acc[iq * 2 + i][j], 0, 0, 0, asc[i], 0, bsc[j]);   \
+        }                                                                                 \
+    }
+#define MX_PHASE(cur, nxt, kt, doload)                                                    \
+    {                                                                                     \
+        if (doload) { MX_ISSUE(nxt, kt, 0) MX_ISSUE(nxt, kt, 1) MX_ISSUE(nxt, kt, 2) MX_ISSUE(nxt, kt, 3) } \
+        MX_STEP(cur)                                                                      \
+    }
+
+    const int nk = a.K / BKB;
+    MX_ISSUE(st0, 0, 0) MX_ISSUE(st0, 0, 1) MX_ISSUE(st0, 0, 2) MX_ISSUE(st0, 0, 3)
+    MX_WAIT_VM0();
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+        MX_PHASE(st0, st1, kt + 1, true)
+        MX_WAIT_VM0();
+        __syncthreads();
+        const bool more = kt + 2 < nk;
+        MX_PHASE(st1, st0, kt + 2, more)
+        MX_WAIT_VM0();
+        __syncthreads();
+    }
+    if (kt < nk) {
+        MX_PHASE(st0, st1, 0, false)
+        __syncthreads();
+    }
+#undef MX_ISSUE
+#undef MX_FRAG
+#undef MX_STEP
+#undef MX_PHASE
+
+    // ---- epilogue: each wave transposes its tiles through a private LDS strip (32 rows x 64 columns
+    //      fp32) so that global memory sees 16-byte accesses; only the owning wave touches its strip
+    constexpr int EP = 68;
+    float *stg = (float *)((wave < 4 ? st0 : st1) + (wave & 3) * (32 * EP * 4));
+    const int er = lane >> 3, ec = (lane & 7) * 8;
+    const int gcol = n0 + wn * 64 + ec;
+    float bias8[8];
+    {
+        bf16x8 b8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b8[i] = f2bf(0.f);
+        if (a.bias && gcol < a.N) b8 = *(const bf16x8 *)(a.bias + gcol);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bias8[i] = bf2f(b8[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    stg[(h * 16 + 4 * kg + e) * EP + j * 16 + r16] = acc[2 * i + h][j][e];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int rl = it * 8 + er;
+            const float4 p0 = *(const float4 *)(stg + rl * EP + ec);
+            const float4 p1 = *(const float4 *)(stg + rl * EP + ec + 4);
+            const float v[8] = {p0.x + bias8[0], p0.y + bias8[1], p0.z + bias8[2], p0.w + bias8[3],
+                                p1.x + bias8[4], p1.y + bias8[5], p1.z + bias8[6], p1.w + bias8[7]};
+            const int row = m0 + wm * 128 + i * 32 + rl;
+            if (row < a.M && gcol < a.N) {
+                bf16x8 w;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) w[q] = f2bf(v[q]);
+                *(bf16x8 *)(a.out + (size_t)row * a.N + gcol) = w;
+            }
+        }
+    }
+}
+
+bool aligned(const void *p, uintptr_t n) { return (((uintptr_t)p) & (n - 1)) == 0; }
+
+}  // namespace
+
+int slora_mx_quantize(int64_t M, int32_t K, const void *x, int64_t ldx, void *codes, void *scales, void *stream)
+{
+    if (M <= 0 || K <= 0 || (K % 32) || ldx < K || (ldx % 8) || !x || !codes || !scales) return SLORA_EINVAL;
+    if (!aligned(x, 16) || !aligned(codes, 8)) return SLORA_EINVAL;
+    const long long threads = (long long)M * (K / 8);
+    if (threads > (1ll << 31) * 256ll) return SLORA_EINVAL;
+    const unsigned grid = (unsigned)((threads + 255) / 256);
+    hipLaunchKernelGGL(mx_quantize_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const bf16 *)x,
+                       (long long)ldx, (long long)M, (int)K, (unsigned char *)codes, (unsigned char *)scales);
+    SL_CHECK_LAUNCH("mx_quantize");
+    return SLORA_OK;
+}
+
+int slora_mx_dequantize(int64_t M, int32_t K, const void *codes, const void *scales, void *y, int64_t ldy,
+                        void *stream)
+{
+    if (M <= 0 || K <= 0 || (K % 32) || ldy < K || (ldy % 8) || !y || !codes || !scales) return SLORA_EINVAL;
+    if (!aligned(y, 16) || !aligned(codes, 8)) return SLORA_EINVAL;
+    const long long threads = (long long)M * (K / 8);
+    if (threads > (1ll << 31) * 256ll) return SLORA_EINVAL;
+    const unsigned grid = (unsigned)((threads + 255) / 256);
+    hipLaunchKernelGGL(mx_dequantize_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       (const unsigned char *)codes, (const unsigned char *)scales, (long long)M, (int)K, (bf16 *)y,
+                       (long long)ldy);
+    SL_CHECK_LAUNCH("mx_dequantize");
+    return SLORA_OK;
+}
+
+int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void *xq, const void *xs, const void *wq,
+                              const void *ws, const void *bias, void *y, void *stream)
+{
+    if (T <= 0 || n_in <= 0 || n_out <= 0 || (n_in % 128) || (n_out % 8) || !xq || !xs || !wq || !ws || !y)
+        return SLORA_EINVAL;
+    if (!aligned(xq, 16) || !aligned(wq, 16) || !aligned(xs, 4) || !aligned(ws, 4) || !aligned(y, 16) ||
+        (bias && !aligned(bias, 16)))
+        return SLORA_EINVAL;
+    // the copies address both operands with 32-bit byte offsets from their bases
+    if ((unsigned long long)T * n_in >= (1ull << 32) || (unsigned long long)n_out * n_in >= (1ull << 32))
+        return SLORA_EINVAL;
+    MxArgs a;
+    a.X = (const unsigned char *)xq; a.XS = (const unsigned char *)xs;
+    a.W = (const unsigned char *)wq; a.WS = (const unsigned char *)ws;
+    a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
+    a.M = T; a.N = n_out; a.K = n_in;
+    const int nb = ((T + BM - 1) / BM) * ((n_out + BN - 1) / BN);
+    const int grid = ((nb + 7) / 8) * 8;
+    hipLaunchKernelGGL(gemm_mx_kernel, dim3(grid), dim3(NTHR), 0, (hipStream_t)stream, a);
+    SL_CHECK_LAUNCH("gemm_mx");
+    return SLORA_OK;
+}

@@ -156,6 +156,24 @@ def test_loss_head_argument_checks():
     assert e.value.code == B.SLORA_ENOSPC
 
 
+def test_mx_argument_checks():
+    """every check of the MXFP8 entry points precedes the first launch (include/slora.h)"""
+    L = B.lib()
+    ok = 4096          # a non-NULL, 16-byte aligned stand-in; no call below reaches a kernel
+    assert L.slora_mx_quantize(4, 48, ok, 48, ok, ok, None) == B.SLORA_EINVAL            # K not a multiple of 32
+    assert L.slora_mx_quantize(4, 64, ok, 32, ok, ok, None) == B.SLORA_EINVAL            # ldx < K
+    assert L.slora_mx_quantize(4, 64, None, 64, ok, ok, None) == B.SLORA_EINVAL
+    assert L.slora_mx_quantize(0, 64, ok, 64, ok, ok, None) == B.SLORA_EINVAL
+    assert L.slora_mx_quantize(4, 64, ok + 2, 64, ok, ok, None) == B.SLORA_EINVAL        # misaligned source
+    assert L.slora_mx_dequantize(4, 64, ok, ok, ok, 60, None) == B.SLORA_EINVAL
+    assert L.slora_mx_dequantize(4, 64, ok, None, ok, 64, None) == B.SLORA_EINVAL
+    assert L.slora_frozen_linear_mxfp8(8, 64, 8, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL    # n_in % 128
+    assert L.slora_frozen_linear_mxfp8(8, 128, 12, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL  # n_out % 8
+    assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok, None, ok, ok, None, ok, None) == B.SLORA_EINVAL
+    assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok + 8, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL
+    assert L.slora_frozen_linear_mxfp8(1 << 22, 1024, 8, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL   # 2^32 bytes
+
+
 def test_strerror():
     L = B.lib()
     assert L.slora_strerror(0) == b"ok"

@@ -1,0 +1,168 @@
+"""GPU parity of the MXFP8 conversion kernels and the quantised frozen linear (Sec. V-B) through the C ABI.
+
+Codes and scales are integer work: bit-exact against the oracle.  The linear layer runs on the codes the
+ORACLE produced (so both sides multiply the same numbers); its bf16 output carries one rounding
+(up to 2^-8 relative) plus the fp32 accumulation of the matrix cores, hence the max-norm relative bound MX_TOL."""
+import numpy as np
+import pytest
+
+from oracle import mx
+from paper_2407_00952_amd import binding as B
+from paper_2407_00952_amd import synth
+from gpu_util import relerr, say
+
+pytestmark = pytest.mark.gpu
+
+# bf16 store: half an ulp is up to 2^-8 of the value (8 significant bits); the fp32 accumulation of the
+# matrix cores adds well under 2^-10 (measured 1.6e-3 in total on full-range random codes): 2^-7 bounds both
+MX_TOL = 2.0 ** -7
+
+
+def _quantize_gpu(x, ldx=None):
+    import torch
+    M, K = x.shape
+    ldx = ldx or K
+    buf = np.zeros((M, ldx), dtype=np.float32)
+    buf[:, :K] = x
+    xd = B.to_device_bf16(buf)
+    codes = torch.empty((M, K), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((M, K // 32), dtype=torch.uint8, device="cuda")
+    B.slora_mx_quantize(M, K, xd, ldx, codes, scales)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy(), scales.cpu().numpy()
+
+
+@pytest.mark.parametrize("M,K,ldx", [(64, 128, None), (700, 320, 328), (1, 32, 40), (333, 1024, None)])
+def test_quantize_bit_exact(M, K, ldx):
+    say("mx quantize", M, K, ldx)
+    x = synth.make_mx_linear_inputs(M, K, 8, seed=synth.BASE_SEED + M)["x"]
+    # the whole dynamic range in one tensor: rows scaled by powers of two from 2^-130 to 2^120, a zero row,
+    # ties (values exactly between two codes after scaling) and values that clamp
+    rng = np.random.default_rng(M)
+    x = x * np.exp2(rng.integers(-20, 20, size=(M, 1))).astype(np.float32)
+    if M >= 64:
+        x[3] *= np.float32(2.0 ** -100); x[4] *= np.float32(2.0 ** 100); x[5] = 0.0
+        x[6] *= np.float32(2.0 ** -126)
+        x[7, :32] = synth.round_bf16(np.concatenate([[1.875, 1.75, 1.8125], 3 * 2.0 ** -17 * np.ones(1), 2.5 * 2.0 ** -17 * np.ones(1),
+                                                     3.5 * 2.0 ** -17 * np.ones(1), np.zeros(26)]).astype(np.float32))
+    x = synth.round_bf16(x.astype(np.float32))
+    q, s = _quantize_gpu(x, ldx)
+    qo, so_ = mx.mx_quantize(x)
+    np.testing.assert_array_equal(s, so_)
+    np.testing.assert_array_equal(q, qo)
+
+
+def test_dequantize_bit_exact_and_roundtrip():
+    import torch
+    say("mx dequantize")
+    rng = np.random.default_rng(5)
+    M, K = 300, 256
+    codes = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x7E                     # no NaN codes
+    scales = rng.integers(90, 160, (M, K // 32)).astype(np.uint8)
+    scales[0, :] = 0; scales[1, :] = 254; scales[2, :] = 127
+    y = torch.zeros((M, K + 8), dtype=torch.bfloat16, device="cuda")
+    B.slora_mx_dequantize(M, K, torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(), y, K + 8)
+    torch.cuda.synchronize()
+    got = B.from_device_bf16(y)[:, :K]
+    want = mx.mx_dequantize(codes, scales)
+    with np.errstate(over="ignore"):
+        want_bf = synth.round_bf16(want.astype(np.float32))
+    np.testing.assert_array_equal(got.view(np.uint32), want_bf.view(np.uint32))
+    # in bf16's range the map is exact and quantising again returns the same codes
+    sel = slice(3, None)
+    assert (got[sel].astype(np.float64) == want[sel]).all()
+    q2, s2 = _quantize_gpu(got[sel])
+    qo, so_ = mx.mx_quantize(got[sel])
+    np.testing.assert_array_equal(q2, qo); np.testing.assert_array_equal(s2, so_)
+
+
+def _linear_gpu(xq, xs, wq, ws, bias):
+    import torch
+    T, K = xq.shape
+    N = wq.shape[0]
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    b = None if bias is None else B.to_device_bf16(bias)
+    B.slora_frozen_linear_mxfp8(T, K, N, t(xq), t(xs), t(wq), t(ws), b, y)
+    torch.cuda.synchronize()
+    return B.from_device_bf16(y)
+
+
+@pytest.mark.parametrize("T,K,N,with_bias", [
+    (256, 128, 256, True),        # one tile, one slab
+    (700, 384, 320, True),        # ragged row and column tiles, odd number of slabs
+    (1024, 768, 768, False),      # the single-layer configuration's shape
+    (513, 1024, 264, True),       # one row and one column piece past a tile
+])
+def test_linear_on_oracle_codes(T, K, N, with_bias):
+    say("mx linear", T, K, N)
+    d = synth.make_mx_linear_inputs(T, K, N, seed=synth.BASE_SEED + T + N)
+    xq, xs = mx.mx_quantize(d["x"])
+    wq, ws = mx.mx_quantize(d["W"])
+    bias = d["bias"] if with_bias else None
+    got = _linear_gpu(xq, xs, wq, ws, bias)
+    ref = mx.mx_linear(xq, xs, wq, ws, bias)
+    e = relerr(got, ref)
+    say("   max-norm relative error %.2e" % e)
+    assert e <= MX_TOL
+    # what the compression costs against the uncompressed layer: element noise 2^-4/sqrt(3) (3 mantissa
+    # bits, uniform in the binade) on both operands, averaged over K products
+    exact = d["x"].astype(np.float64) @ d["W"].astype(np.float64).T + (0 if bias is None else bias.astype(np.float64))
+    rms = np.sqrt(((got - exact) ** 2).mean() / (exact ** 2).mean())
+    say("   rms error against the uncompressed layer %.3f" % rms)
+    assert rms < 0.06
+
+
+def test_linear_full_code_range():
+    """every finite element code and a wide band of scales: the hardware's decode and block scaling"""
+    say("mx linear, random codes")
+    rng = np.random.default_rng(9)
+    T, K, N = 256, 256, 256
+    def codes(shape):
+        c = rng.integers(0, 256, shape).astype(np.uint8)
+        c[(c & 0x7F) == 0x7F] = 0x01
+        return c
+    xq, wq = codes((T, K)), codes((N, K))
+    xq[0, :256] = np.arange(256, dtype=np.uint8); xq[0, 0x7F] = 0; xq[0, 0xFF] = 0
+    xs = rng.integers(110, 140, (T, K // 32)).astype(np.uint8)
+    ws = rng.integers(110, 140, (N, K // 32)).astype(np.uint8)
+    got = _linear_gpu(xq, xs, wq, ws, None)
+    ref = mx.mx_linear(xq, xs, wq, ws, None)
+    e = relerr(got, ref)
+    say("   max-norm relative error %.2e" % e)
+    assert e <= MX_TOL
+    # row-wise too: each row's own scale spread must come through
+    rowerr = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    assert rowerr.max() <= 2 * MX_TOL, rowerr.max()
+
+
+def test_linear_full_size_sampled():
+    """the FC shape of the metric's workload, checked on sampled outputs the oracle computes one by one"""
+    import torch
+    say("mx linear 32768 x 1024 x 4096 sampled")
+    T, K, N = 32768, 1024, 4096
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    x = torch.randn((T, K), device="cuda", generator=g).to(torch.bfloat16)
+    W = (torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    xq = torch.empty((T, K), dtype=torch.uint8, device="cuda"); xs = torch.empty((T, K // 32), dtype=torch.uint8, device="cuda")
+    wq = torch.empty((N, K), dtype=torch.uint8, device="cuda"); ws = torch.empty((N, K // 32), dtype=torch.uint8, device="cuda")
+    B.slora_mx_quantize(T, K, x, K, xq, xs)
+    B.slora_mx_quantize(N, K, W, K, wq, ws)
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    B.slora_frozen_linear_mxfp8(T, K, N, xq, xs, wq, ws, None, y)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(12)
+    rows = np.unique(np.concatenate([rng.integers(0, T, 48), [0, 255, 256, T - 1]]))
+    cols = np.unique(np.concatenate([rng.integers(0, N, 64), [0, 255, 256, N - 1]]))
+    xr = x[rows].float().cpu().numpy(); Wc = W[cols].float().cpu().numpy()
+    # the conversion at full size: the sampled rows' codes against the oracle's, bit for bit
+    qo, so_ = mx.mx_quantize(xr)
+    np.testing.assert_array_equal(xq[rows].cpu().numpy(), qo); np.testing.assert_array_equal(xs[rows].cpu().numpy(), so_)
+    qw, sw = mx.mx_quantize(Wc)
+    np.testing.assert_array_equal(wq[cols].cpu().numpy(), qw); np.testing.assert_array_equal(ws[cols].cpu().numpy(), sw)
+    ref = mx.mx_linear(qo, so_, qw, sw)
+    got = y[rows][:, cols].float().cpu().numpy()
+    e = relerr(got, ref)
+    say("   max-norm relative error on %d sampled outputs %.2e" % (ref.size, e))
+    assert e <= MX_TOL
