@@ -110,3 +110,28 @@ def mx_linear(xq, xs, wq, ws, bias=None):
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float64)[None, :]
     return y
+
+
+def mx_lora_linear_fwd(x, W, bias, A, B, s):
+    """LoRA-adapted linear layer (Sec. II-C) with the frozen product in MXFP8 and the adapter exact:
+        y = deq(Q(x)) . deq(Q(W))^T + bias + s (x A^T) B^T
+    x [T,in] and W [out,in] are quantised along the contraction axis `in`; the low-rank branch sees the
+    unquantised x ("LoRA kept in higher precision")."""
+    x, W = np.asarray(x, dtype=np.float64), np.asarray(W, dtype=np.float64)
+    A, B = np.asarray(A, dtype=np.float64), np.asarray(B, dtype=np.float64)
+    y = mx_linear(*mx_quantize(x), *mx_quantize(W), bias)
+    return y + s * ((x @ A.T) @ B.T)
+
+
+def mx_lora_linear_bwd(x, dy, W, A, B, s):
+    """The backward pass taken by the compressed layer (no weight gradient: W is frozen):
+        dx = deq(Q(dy)) . deq(Q(W^T))^T + s (dy B) A        both operands quantised along `out`
+        dA = s (dy B)^T x            dB = s dy^T (x A^T)    from the unquantised x and dy
+    W^T is quantised on its own (its blocks run along the other axis), so dx is the straight-through
+    input gradient, not the exact derivative of the quantised forward."""
+    x, dy, W = (np.asarray(t, dtype=np.float64) for t in (x, dy, W))
+    A, B = np.asarray(A, dtype=np.float64), np.asarray(B, dtype=np.float64)
+    dx = mx_linear(*mx_quantize(dy), *mx_quantize(W.T.copy()), None) + s * ((dy @ B) @ A)
+    dA = s * (dy @ B).T @ x
+    dB = s * dy.T @ (x @ A.T)
+    return dx, dA, dB

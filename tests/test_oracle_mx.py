@@ -163,3 +163,62 @@ def test_rejects_bad_input():
         mx.mx_quantize(np.zeros((2, 48)))
     with pytest.raises(ValueError):
         mx.mx_quantize(np.array([[np.inf] + [0.0] * 31]))
+
+
+def _representable(rng, shape):
+    """values that MXFP8 stores exactly: E4M3 codes times a per-block power of two, every block's largest
+    magnitude 448 so that quantising returns the same codes"""
+    codes = rng.integers(0, 127, shape).astype(np.uint8) | (rng.integers(0, 2, shape).astype(np.uint8) << 7)
+    codes[..., ::32] = 0x7E
+    sc = rng.integers(115, 125, shape[:-1] + (shape[-1] // 32,)).astype(np.uint8)
+    return mx.mx_dequantize(codes, sc)
+
+
+def test_lora_linear_equals_the_exact_layer_on_representable_data():
+    """where nothing is lost to quantisation the compressed layer IS the exact LoRA layer (pinned on its
+    own in test_oracle_linear.py): catches a wrong transpose, a dropped term or a misplaced s"""
+    from oracle import slora_oracle as so
+    rng = np.random.default_rng(6)
+    T, n_in, n_out, r, s = 24, 64, 96, 3, 32.0 / 3
+    x = _representable(rng, (T, n_in))
+    dy = _representable(rng, (T, n_out))
+    # W must be representable along BOTH axes (it is quantised as W and as W^T): a power of two per
+    # 32 x 32 tile times E4M3 values, every row and column of a tile reaching 448
+    Wc = rng.integers(1, 127, (n_out, n_in)).astype(np.uint8)
+    W = mx.e4m3_decode(Wc)
+    for i in range(0, n_out, 32):
+        for j in range(0, n_in, 32):
+            tile = W[i:i + 32, j:j + 32]
+            np.fill_diagonal(tile, 448.0)
+            tile *= 2.0 ** rng.integers(-12, -6)
+    b = rng.normal(0, 1, n_out)
+    A = rng.normal(0, 0.1, (r, n_in)); B = rng.normal(0, 0.1, (n_out, r))
+    y = mx.mx_lora_linear_fwd(x, W, b, A, B, s)
+    y_ref, _ = so.lora_linear_fwd(x, W, b, A, B, s)
+    np.testing.assert_allclose(y, y_ref, rtol=1e-12, atol=1e-12)
+    dx, dA, dB = mx.mx_lora_linear_bwd(x, dy, W, A, B, s)
+    dx_ref, dA_ref, dB_ref = so.lora_linear_bwd(x, dy, W, A, B, s)
+    np.testing.assert_allclose(dx, dx_ref, rtol=1e-12, atol=1e-9)
+    np.testing.assert_allclose(dA, dA_ref, rtol=1e-12, atol=1e-9)
+    np.testing.assert_allclose(dB, dB_ref, rtol=1e-12, atol=1e-9)
+
+
+def test_lora_linear_noise_budget_and_reductions():
+    from oracle import slora_oracle as so
+    from paper_2407_00952_amd import synth
+    c = synth.make_single_layer(T=128, n_in=256, n_out=128, r=4)
+    s = c["alpha"] / c["r"]
+    y = mx.mx_lora_linear_fwd(c["x"], c["W"], c["b"], c["A"], c["B"], s)
+    y_ref, _ = so.lora_linear_fwd(c["x"], c["W"], c["b"], c["A"], c["B"], s)
+    dx, dA, dB = mx.mx_lora_linear_bwd(c["x"], c["dy"], c["W"], c["A"], c["B"], s)
+    dx_ref, dA_ref, dB_ref = so.lora_linear_bwd(c["x"], c["dy"], c["W"], c["A"], c["B"], s)
+    rms = lambda a, b: np.sqrt(((a - b) ** 2).mean() / (b ** 2).mean())
+    # two operands with 2^-4/sqrt(3) relative element noise each: about 5 % of the product's rms
+    assert 0.01 < rms(y, y_ref) < 0.07 and 0.01 < rms(dx, dx_ref) < 0.07
+    # the adapter gradients never see the quantised operands
+    np.testing.assert_allclose(dA, dA_ref, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dB, dB_ref, rtol=1e-12, atol=1e-12)
+    # without an adapter the layer is the quantised linear
+    Z = np.zeros_like(c["B"])
+    np.testing.assert_array_equal(mx.mx_lora_linear_fwd(c["x"], c["W"], c["b"], c["A"], Z, s),
+                                  mx.mx_linear(*mx.mx_quantize(c["x"]), *mx.mx_quantize(c["W"]), c["b"]))
