@@ -215,6 +215,34 @@ int slora_mx_dequantize(int64_t M, int32_t K, const void *codes, const void *sca
 int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void *xq, const void *xs,
                               const void *wq, const void *ws, const void *bias, void *y, void *stream);
 
+/* One LoRA-adapted linear layer (Sec. II-C) with the frozen product in MXFP8 and the adapter kept in bf16
+ * operands / fp32 parameters:
+ *   fwd:  y  = deq(Q(x)) . deq(Q(W))^T + bias + s (x A^T) B^T            s = alpha / r
+ *   bwd:  dx = deq(Q(dy)) . deq(Q(W^T))^T + s (dy B) A                   (straight-through; never dW)
+ *         dA = s (dy B)^T x        dB = s dy^T (x A^T)                    from the unquantised x, dy
+ * Q quantises along the contraction axis of the product it feeds: x and W along n_in, dy and W^T along
+ * n_out (W^T is quantised on its own).  The frozen weight is packed once:
+ * slora_mx_weight_bytes:  size of the packed form (both orientations plus packing scratch), 0 if the
+ *                         shape is unsupported.
+ * slora_mx_pack_weight:   W bf16 [n_out, n_in] dense (16-byte aligned) -> packed (256-byte aligned,
+ *                         at least slora_mx_weight_bytes).  The packed buffer is read-only afterwards.
+ * slora_mx_lora_linear_ws_bytes / _fwd / _bwd: x bf16 [T, n_in], dy bf16 [T, n_out], bias bf16 [n_out] or
+ *                         NULL, A fp32 [r, n_in], B fp32 [n_out, r]; outputs y bf16 [T, n_out], dx bf16
+ *                         [T, n_in], dA fp32 [r, n_in], dB fp32 [n_out, r] (overwritten); ws caller-owned,
+ *                         256-byte aligned, holds the quantised activations and the rank-space
+ *                         intermediates; bwd does not need a preceding fwd.
+ * n_in and n_out multiples of 128, 1 <= r <= SLORA_MAX_RANK, T * max(n_in, n_out) and n_in * n_out below
+ * 2^31.  Errors: SLORA_EINVAL, SLORA_ENOSPC (ws or packed buffer too small), SLORA_EHIP. */
+size_t slora_mx_weight_bytes(int32_t n_in, int32_t n_out);
+int slora_mx_pack_weight(int32_t n_in, int32_t n_out, const void *W, void *packed, size_t bytes, void *stream);
+size_t slora_mx_lora_linear_ws_bytes(int32_t T, int32_t n_in, int32_t n_out, int32_t r);
+int slora_mx_lora_linear_fwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, float alpha, const void *x,
+                             const void *packed_w, const void *bias, const float *A, const float *B, void *y,
+                             void *ws, size_t ws_bytes, void *stream);
+int slora_mx_lora_linear_bwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, float alpha, const void *x,
+                             const void *dy, const void *packed_w, const float *A, const float *B, void *dx,
+                             float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- measurement hook (not part of the method) ---------------------------------------------------- */
 /* While enabled, every launch of the bf16 GEMM kernel (the frozen products of Sec. II-C with the
  * fused low-rank branch) is bracketed by HIP events on its stream.  slora_prof_read waits for the

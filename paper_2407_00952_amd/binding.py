@@ -29,7 +29,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_prof_read", "slora_frozen_linear_bf16", "slora_loss_head_ws_bytes",
            "slora_loss_head_prepare", "slora_loss_head", "slora_client_fwd", "slora_client_bwd",
            "slora_adapters_changed", "slora_adamw", "slora_mx_quantize", "slora_mx_dequantize",
-           "slora_frozen_linear_mxfp8"]
+           "slora_frozen_linear_mxfp8", "slora_mx_weight_bytes", "slora_mx_pack_weight",
+           "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd"]
 
 
 class slora_config(ctypes.Structure):
@@ -84,6 +85,13 @@ def lib():
         L.slora_mx_quantize.argtypes = [i64, i32, vp, i64, vp, vp, vp]
         L.slora_mx_dequantize.argtypes = [i64, i32, vp, vp, vp, i64, vp]
         L.slora_frozen_linear_mxfp8.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.slora_mx_weight_bytes.argtypes = [i32, i32]
+        L.slora_mx_weight_bytes.restype = sz
+        L.slora_mx_pack_weight.argtypes = [i32, i32, vp, vp, sz, vp]
+        L.slora_mx_lora_linear_ws_bytes.argtypes = [i32, i32, i32, i32]
+        L.slora_mx_lora_linear_ws_bytes.restype = sz
+        L.slora_mx_lora_linear_fwd.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slora_mx_lora_linear_bwd.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_prof_enable.argtypes = [i32]
         L.slora_prof_read.argtypes = [vp, vp, vp]
         L.slora_strerror.argtypes = [i32]
@@ -202,6 +210,28 @@ def slora_mx_dequantize(M, K, codes, scales, y, ldy, stream=None):
 def slora_frozen_linear_mxfp8(T, n_in, n_out, xq, xs, wq, ws, bias, y, stream=None):
     _check(lib().slora_frozen_linear_mxfp8(T, n_in, n_out, _p(xq), _p(xs), _p(wq), _p(ws), _p(bias), _p(y),
                                            _stream(stream)))
+
+
+def slora_mx_weight_bytes(n_in, n_out):
+    return int(lib().slora_mx_weight_bytes(n_in, n_out))
+
+
+def slora_mx_pack_weight(n_in, n_out, W, packed, nbytes, stream=None):
+    _check(lib().slora_mx_pack_weight(n_in, n_out, _p(W), _p(packed), nbytes, _stream(stream)))
+
+
+def slora_mx_lora_linear_ws_bytes(T, n_in, n_out, r):
+    return int(lib().slora_mx_lora_linear_ws_bytes(T, n_in, n_out, r))
+
+
+def slora_mx_lora_linear_fwd(T, n_in, n_out, r, alpha, x, packed_w, bias, A, B, y, ws, ws_bytes, stream=None):
+    _check(lib().slora_mx_lora_linear_fwd(T, n_in, n_out, r, alpha, _p(x), _p(packed_w), _p(bias), _p(A), _p(B),
+                                          _p(y), _p(ws), ws_bytes, _stream(stream)))
+
+
+def slora_mx_lora_linear_bwd(T, n_in, n_out, r, alpha, x, dy, packed_w, A, B, dx, dA, dB, ws, ws_bytes, stream=None):
+    _check(lib().slora_mx_lora_linear_bwd(T, n_in, n_out, r, alpha, _p(x), _p(dy), _p(packed_w), _p(A), _p(B),
+                                          _p(dx), _p(dA), _p(dB), _p(ws), ws_bytes, _stream(stream)))
 
 
 def slora_client_fwd(ctx, batch, tokens, vocab, wte, wpe, act, stream=None):

@@ -123,6 +123,9 @@ struct MxArgs {
     const bf16 *bias;                // [N] or null
     bf16 *out;                       // [M,N]
     int M, N, K;
+    // low-rank branch kept in bf16 (null zs = none): out += zs . tmat^T
+    const bf16 *zs;                  // [M,16]: scaled rank-space activations, zero beyond the rank
+    const bf16 *tmat;                // [N,32]: up-projection, zero beyond the rank
 };
 
 __device__ __forceinline__ void glds16(const void *sbase, unsigned voff, unsigned lds)
@@ -268,6 +271,29 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
 #undef MX_STEP
 #undef MX_PHASE
 
+    // ---- low-rank tail (SplitLoRA Sec. II-C: W + BA with the adapter kept in bf16): one bf16 MFMA k-step
+    //      of 32 per tile on operands read straight from global memory (1 MB and 256 KB: cache hits);
+    //      k = 16..31 of both operands is zero padding
+    if (a.zs != nullptr) {
+        bf16x8 tb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = min(n0 + wn * 64 + j * 16 + r16, a.N - 1);
+            tb[j] = *(const bf16x8 *)(a.tmat + (size_t)n * 32 + kg * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = min(m0 + wm * 128 + i * 16 + r16, a.M - 1);
+            bf16x8 za;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) za[q] = f2bf(0.f);
+            if (kg < 2) za = *(const bf16x8 *)(a.zs + (size_t)row * 16 + kg * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(za, tb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
     // ---- epilogue: each wave transposes its tiles through a private LDS strip (32 rows x 64 columns
     //      fp32) so that global memory sees 16-byte accesses; only the owning wave touches its strip
     constexpr int EP = 68;
@@ -310,7 +336,118 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
     }
 }
 
+// Rank-space activations of the bf16 adapter branch: out[M,16] = scale * X[M,K] . Z[16,K]^T (rows of Z
+// beyond the rank are zero), rounded to bf16.  One wave per 16 rows, operands straight from global memory
+// (the kernel reads X once: HBM-bound), four independent accumulators for the four k-steps in flight.
+__global__ __launch_bounds__(256) void rank_project_kernel(const bf16 *__restrict__ X, long long ldx, int M, int K,
+                                                           const bf16 *__restrict__ Z, float scale,
+                                                           bf16 *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15, kg = lane >> 4;
+    const int row0 = (blockIdx.x * 4 + wave) * 16;
+    if (row0 >= M) return;
+    const bf16 *xp = X + (size_t)min(row0 + r16, M - 1) * ldx + kg * 8;
+    const bf16 *zp = Z + (size_t)r16 * K + kg * 8;
+    f32x4 acc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[u][e] = 0.f;
+    int k0 = 0;
+    for (; k0 + 128 <= K; k0 += 128) {
+        bf16x8 xa[4], zb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            xa[u] = *(const bf16x8 *)(xp + k0 + u * 32);
+            zb[u] = *(const bf16x8 *)(zp + k0 + u * 32);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[u], zb[u], acc[u], 0, 0, 0);
+    }
+    for (; k0 < K; k0 += 32)
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8 *)(xp + k0), *(const bf16x8 *)(zp + k0), acc[0],
+                                                         0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int row = row0 + 4 * kg + e;
+        const float v = ((acc[0][e] + acc[1][e]) + (acc[2][e] + acc[3][e])) * scale;
+        if (row < M) out[(size_t)row * 16 + r16] = f2bf(v);
+    }
+}
+
 bool aligned(const void *p, uintptr_t n) { return (((uintptr_t)p) & (n - 1)) == 0; }
+inline size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int launch_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned char *codes, unsigned char *scales,
+                    hipStream_t st)
+{
+    const long long threads = M * (K / 8);
+    hipLaunchKernelGGL(mx_quantize_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, x, ldx, M, K,
+                       codes, scales);
+    SL_CHECK_LAUNCH("mx_quantize");
+    return 0;
+}
+
+int launch_gemm_mx(const MxArgs &a, hipStream_t st)
+{
+    const int nb = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    hipLaunchKernelGGL(gemm_mx_kernel, dim3(((nb + 7) / 8) * 8), dim3(NTHR), 0, st, a);
+    SL_CHECK_LAUNCH("gemm_mx");
+    return 0;
+}
+
+int launch_rank_project(const bf16 *X, long long ldx, int M, int K, const bf16 *Z, float scale, bf16 *out,
+                        hipStream_t st)
+{
+    hipLaunchKernelGGL(rank_project_kernel, dim3((M + 63) / 64), dim3(256), 0, st, X, ldx, M, K, Z, scale, out);
+    SL_CHECK_LAUNCH("rank_project");
+    return 0;
+}
+
+// packed frozen weight: codes and scales of W [n_out, n_in] (blocks along n_in, for the forward product)
+// and of W^T [n_in, n_out] (blocks along n_out, for the input-gradient product), then packing scratch
+struct MxPack { size_t wq, ws, tq, ts, scratch, total; };
+MxPack mx_pack(int n_in, int n_out)
+{
+    MxPack p;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = al256(off + bytes); return o; };
+    p.wq = take((size_t)n_out * n_in);
+    p.ws = take((size_t)n_out * n_in / 32);
+    p.tq = take((size_t)n_in * n_out);
+    p.ts = take((size_t)n_in * n_out / 32);
+    p.scratch = take(2 * (size_t)n_in * n_out);
+    p.total = off;
+    return p;
+}
+
+struct MxLinWs { size_t A16, B32, B16T, A32T, zs, ps, q, qs, part, total; };
+MxLinWs mx_lin_ws(int T, int n_in, int n_out)
+{
+    MxLinWs w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = al256(off + bytes); return o; };
+    const size_t nmax = n_in > n_out ? n_in : n_out;
+    w.A16 = take(2 * 16 * (size_t)n_in);
+    w.B32 = take(2 * (size_t)n_out * 32);
+    w.B16T = take(2 * 16 * (size_t)n_out);
+    w.A32T = take(2 * (size_t)n_in * 32);
+    w.zs = take(2 * (size_t)T * 16);
+    w.ps = take(2 * (size_t)T * 16);
+    w.q = take((size_t)T * nmax);
+    w.qs = take((size_t)T * nmax / 32);
+    w.part = take(4 * lora_grad_partial_floats(T, (int)nmax));
+    w.total = off;
+    return w;
+}
+
+bool mx_lin_args_ok(int T, int n_in, int n_out, int r)
+{
+    if (T <= 0 || n_in <= 0 || n_out <= 0 || r < 1 || r > SLORA_MAX_RANK) return false;
+    if ((n_in % 128) || (n_out % 128)) return false;
+    const unsigned long long nmax = n_in > n_out ? n_in : n_out;
+    return (unsigned long long)T * nmax < (1ull << 31) && (unsigned long long)n_in * n_out < (1ull << 31);
+}
 
 }  // namespace
 
@@ -318,13 +455,9 @@ int slora_mx_quantize(int64_t M, int32_t K, const void *x, int64_t ldx, void *co
 {
     if (M <= 0 || K <= 0 || (K % 32) || ldx < K || (ldx % 8) || !x || !codes || !scales) return SLORA_EINVAL;
     if (!aligned(x, 16) || !aligned(codes, 8)) return SLORA_EINVAL;
-    const long long threads = (long long)M * (K / 8);
-    if (threads > (1ll << 31) * 256ll) return SLORA_EINVAL;
-    const unsigned grid = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL(mx_quantize_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const bf16 *)x,
-                       (long long)ldx, (long long)M, (int)K, (unsigned char *)codes, (unsigned char *)scales);
-    SL_CHECK_LAUNCH("mx_quantize");
-    return SLORA_OK;
+    if ((long long)M * (K / 8) > (1ll << 31) * 256ll) return SLORA_EINVAL;
+    return launch_quantize((const bf16 *)x, ldx, M, K, (unsigned char *)codes, (unsigned char *)scales,
+                           (hipStream_t)stream);
 }
 
 int slora_mx_dequantize(int64_t M, int32_t K, const void *codes, const void *scales, void *y, int64_t ldy,
@@ -358,9 +491,102 @@ int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void
     a.W = (const unsigned char *)wq; a.WS = (const unsigned char *)ws;
     a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
     a.M = T; a.N = n_out; a.K = n_in;
-    const int nb = ((T + BM - 1) / BM) * ((n_out + BN - 1) / BN);
-    const int grid = ((nb + 7) / 8) * 8;
-    hipLaunchKernelGGL(gemm_mx_kernel, dim3(grid), dim3(NTHR), 0, (hipStream_t)stream, a);
-    SL_CHECK_LAUNCH("gemm_mx");
-    return SLORA_OK;
+    a.zs = nullptr; a.tmat = nullptr;
+    return launch_gemm_mx(a, (hipStream_t)stream);
+}
+
+size_t slora_mx_weight_bytes(int32_t n_in, int32_t n_out)
+{
+    if (n_in <= 0 || n_out <= 0 || (n_in % 128) || (n_out % 128)) return 0;
+    return mx_pack(n_in, n_out).total;
+}
+
+int slora_mx_pack_weight(int32_t n_in, int32_t n_out, const void *W, void *packed, size_t bytes, void *stream)
+{
+    if (n_in <= 0 || n_out <= 0 || (n_in % 128) || (n_out % 128) || !W || !packed) return SLORA_EINVAL;
+    if (!aligned(W, 16) || !aligned(packed, 256)) return SLORA_EINVAL;
+    const MxPack p = mx_pack(n_in, n_out);
+    if (bytes < p.total) return SLORA_ENOSPC;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char *base = (unsigned char *)packed;
+    int rc;
+    if ((rc = launch_quantize((const bf16 *)W, n_in, n_out, n_in, base + p.wq, base + p.ws, st))) return rc;
+    bf16 *wt = (bf16 *)(base + p.scratch);
+    if ((rc = launch_transpose_bf16((const bf16 *)W, n_out, n_in, wt, st))) return rc;
+    return launch_quantize(wt, n_out, n_in, n_out, base + p.tq, base + p.ts, st);
+}
+
+size_t slora_mx_lora_linear_ws_bytes(int32_t T, int32_t n_in, int32_t n_out, int32_t r)
+{
+    if (!mx_lin_args_ok(T, n_in, n_out, r)) return 0;
+    return mx_lin_ws(T, n_in, n_out).total;
+}
+
+int slora_mx_lora_linear_fwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, float alpha, const void *x,
+                             const void *packed_w, const void *bias, const float *A, const float *B, void *y,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    if (!mx_lin_args_ok(T, n_in, n_out, r) || !x || !packed_w || !A || !B || !y || !ws) return SLORA_EINVAL;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(packed_w, 256) || !aligned(ws, 256) ||
+        (bias && !aligned(bias, 16)))
+        return SLORA_EINVAL;
+    const MxLinWs w = mx_lin_ws(T, n_in, n_out);
+    if (ws_bytes < w.total) return SLORA_ENOSPC;
+    const MxPack p = mx_pack(n_in, n_out);
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char *base = (unsigned char *)ws;
+    const unsigned char *pw = (const unsigned char *)packed_w;
+    const float s = alpha / (float)r;
+    int rc;
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 16, n_in, 0, st))) return rc;
+    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B32), n_out, 32, 0, st))) return rc;
+    if ((rc = launch_rank_project((const bf16 *)x, n_in, T, n_in, (const bf16 *)(base + w.A16), s,
+                                  (bf16 *)(base + w.zs), st)))
+        return rc;
+    if ((rc = launch_quantize((const bf16 *)x, n_in, T, n_in, base + w.q, base + w.qs, st))) return rc;
+    MxArgs a;
+    a.X = base + w.q; a.XS = base + w.qs; a.W = pw + p.wq; a.WS = pw + p.ws;
+    a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
+    a.M = T; a.N = n_out; a.K = n_in;
+    a.zs = (const bf16 *)(base + w.zs); a.tmat = (const bf16 *)(base + w.B32);
+    return launch_gemm_mx(a, st);
+}
+
+int slora_mx_lora_linear_bwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, float alpha, const void *x,
+                             const void *dy, const void *packed_w, const float *A, const float *B, void *dx,
+                             float *dA, float *dB, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!mx_lin_args_ok(T, n_in, n_out, r) || !x || !dy || !packed_w || !A || !B || !dx || !dA || !dB || !ws)
+        return SLORA_EINVAL;
+    if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dx, 16) || !aligned(packed_w, 256) || !aligned(ws, 256))
+        return SLORA_EINVAL;
+    const MxLinWs w = mx_lin_ws(T, n_in, n_out);
+    if (ws_bytes < w.total) return SLORA_ENOSPC;
+    const MxPack p = mx_pack(n_in, n_out);
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char *base = (unsigned char *)ws;
+    const unsigned char *pw = (const unsigned char *)packed_w;
+    const float s = alpha / (float)r;
+    int rc;
+    // zs = s x A^T (for dB) and ps = s dy B (for dA and for the low-rank part of dx)
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 16, n_in, 0, st))) return rc;
+    if ((rc = launch_rank_project((const bf16 *)x, n_in, T, n_in, (const bf16 *)(base + w.A16), s,
+                                  (bf16 *)(base + w.zs), st)))
+        return rc;
+    if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16T), 16, n_out, 1, st))) return rc;
+    if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A32T), n_in, 32, 1, st))) return rc;
+    if ((rc = launch_rank_project((const bf16 *)dy, n_out, T, n_out, (const bf16 *)(base + w.B16T), s,
+                                  (bf16 *)(base + w.ps), st)))
+        return rc;
+    if ((rc = launch_quantize((const bf16 *)dy, n_out, T, n_out, base + w.q, base + w.qs, st))) return rc;
+    MxArgs a;
+    a.X = base + w.q; a.XS = base + w.qs; a.W = pw + p.tq; a.WS = pw + p.ts;
+    a.bias = nullptr; a.out = (bf16 *)dx;
+    a.M = T; a.N = n_in; a.K = n_out;
+    a.zs = (const bf16 *)(base + w.ps); a.tmat = (const bf16 *)(base + w.A32T);
+    if ((rc = launch_gemm_mx(a, st))) return rc;
+    float *part = (float *)(base + w.part);
+    if ((rc = launch_lora_grad((const bf16 *)x, n_in, n_in, (const bf16 *)(base + w.ps), 16, r, T, part, dA, 1, st)))
+        return rc;
+    return launch_lora_grad((const bf16 *)dy, n_out, n_out, (const bf16 *)(base + w.zs), 16, r, T, part, dB, 0, st);
 }

@@ -172,6 +172,14 @@ def test_mx_argument_checks():
     assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok, None, ok, ok, None, ok, None) == B.SLORA_EINVAL
     assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok + 8, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL
     assert L.slora_frozen_linear_mxfp8(1 << 22, 1024, 8, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL   # 2^32 bytes
+    # the compressed LoRA layer
+    assert L.slora_mx_weight_bytes(100, 128) == 0 and L.slora_mx_weight_bytes(128, 256) > 128 * 256 * 2
+    assert L.slora_mx_lora_linear_ws_bytes(64, 128, 128, 17) == 0 and L.slora_mx_lora_linear_ws_bytes(64, 128, 128, 4) > 0
+    assert L.slora_mx_pack_weight(128, 128, ok, ok, 16, None) == B.SLORA_ENOSPC
+    assert L.slora_mx_pack_weight(128, 64, ok, ok, 1 << 20, None) == B.SLORA_EINVAL
+    assert L.slora_mx_lora_linear_fwd(64, 128, 128, 4, 32.0, ok, ok, None, ok, ok, ok, ok, 16, None) == B.SLORA_ENOSPC
+    assert L.slora_mx_lora_linear_fwd(64, 128, 128, 0, 32.0, ok, ok, None, ok, ok, ok, ok, 1 << 30, None) == B.SLORA_EINVAL
+    assert L.slora_mx_lora_linear_bwd(64, 128, 128, 4, 32.0, ok, None, ok, ok, ok, ok, ok, ok, ok, 1 << 30, None) == B.SLORA_EINVAL
 
 
 def test_strerror():

@@ -9,7 +9,7 @@ import pytest
 from oracle import mx
 from paper_2407_00952_amd import binding as B
 from paper_2407_00952_amd import synth
-from gpu_util import relerr, say
+from gpu_util import BF16_TOL, relerr, say
 
 pytestmark = pytest.mark.gpu
 
@@ -166,3 +166,68 @@ def test_linear_full_size_sampled():
     e = relerr(got, ref)
     say("   max-norm relative error on %d sampled outputs %.2e" % (ref.size, e))
     assert e <= MX_TOL
+
+
+def _aligned_bytes(n):
+    """a uint8 device tensor whose first byte is 256-byte aligned (torch's allocator gives 512)"""
+    import torch
+    t = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+    off = (-t.data_ptr()) % 256
+    return t[off:off + n]
+
+
+def _run_lora_layer(c, bias, r):
+    import torch
+    T, n_in = c["x"].shape
+    n_out = c["W"].shape[0]
+    x, W, dy = (B.to_device_bf16(c[k]) for k in ("x", "W", "dy"))
+    bd = None if bias is None else B.to_device_bf16(bias)
+    A = torch.from_numpy(c["A"]).cuda(); Bm = torch.from_numpy(c["B"]).cuda()
+    nw = B.slora_mx_weight_bytes(n_in, n_out); packed = _aligned_bytes(nw)
+    B.slora_mx_pack_weight(n_in, n_out, W, packed, nw)
+    nws = B.slora_mx_lora_linear_ws_bytes(T, n_in, n_out, r); ws = _aligned_bytes(nws)
+    assert nw > 0 and nws > 0
+    y = torch.empty((T, n_out), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((T, n_in), dtype=torch.bfloat16, device="cuda")
+    dA = torch.empty((r, n_in), dtype=torch.float32, device="cuda")
+    dB = torch.empty((n_out, r), dtype=torch.float32, device="cuda")
+    B.slora_mx_lora_linear_fwd(T, n_in, n_out, r, c["alpha"], x, packed, bd, A, Bm, y, ws, nws)
+    torch.cuda.synchronize()
+    B.slora_mx_lora_linear_bwd(T, n_in, n_out, r, c["alpha"], x, dy, packed, A, Bm, dx, dA, dB, ws, nws)
+    torch.cuda.synchronize()
+    return B.from_device_bf16(y), B.from_device_bf16(dx), dA.cpu().numpy(), dB.cpu().numpy()
+
+
+@pytest.mark.parametrize("T,n_in,n_out,r,with_bias", [
+    (1024, 768, 768, 4, True),       # the single-layer configuration (Sec. IV: GPT-2 small width, r = 4)
+    (700, 384, 256, 3, True),        # ragged rows, odd slab count, rank that is no power of two
+    (300, 256, 640, 16, False),      # full rank, more than two column tiles
+    (512, 1024, 128, 1, True),       # rank 1
+])
+def test_lora_linear_mxfp8(T, n_in, n_out, r, with_bias):
+    say("mx lora linear", T, n_in, n_out, r)
+    c = synth.make_single_layer(T=T, n_in=n_in, n_out=n_out, r=r, seed=synth.BASE_SEED + T + r, quant=True,
+                                bias=with_bias)
+    bias = c["b"]
+    s = c["alpha"] / r
+    # (1) B = 0: only the quantised products are left, in both orientations of the packed weight; they are
+    #     exact up to the bf16 store
+    c0 = dict(c); c0["B"] = np.zeros_like(c["B"])
+    y, dx, dA, dB = _run_lora_layer(c0, bias, r)
+    yo = mx.mx_lora_linear_fwd(c["x"], c["W"], bias, c["A"], c0["B"], s)
+    dxo, dAo, dBo = mx.mx_lora_linear_bwd(c["x"], c["dy"], c["W"], c["A"], c0["B"], s)
+    e = {"y": relerr(y, yo), "dx": relerr(dx, dxo), "dB": relerr(dB, dBo)}
+    say("   B = 0: " + ", ".join("%s=%.2e" % kv for kv in e.items()))
+    assert e["y"] <= MX_TOL and e["dx"] <= MX_TOL and e["dB"] <= BF16_TOL and np.abs(dA).max() == 0.0
+    # (2) the adapter made large (B ~ N(0, 0.1^2)) so that the low-rank term is visible next to x W^T.  Its
+    #     operands A, B, s x A^T and s dy B are rounded to bf16 as in the uncompressed layer: same bound
+    c["B"] = synth.round_bf16(c["B"] * 10)
+    y, dx, dA, dB = _run_lora_layer(c, bias, r)
+    yo = mx.mx_lora_linear_fwd(c["x"], c["W"], bias, c["A"], c["B"], s)
+    dxo, dAo, dBo = mx.mx_lora_linear_bwd(c["x"], c["dy"], c["W"], c["A"], c["B"], s)
+    e = {"y": relerr(y, yo), "dx": relerr(dx, dxo), "dA": relerr(dA, dAo), "dB": relerr(dB, dBo)}
+    say("   B x 10: " + ", ".join("%s=%.2e" % kv for kv in e.items()))
+    assert max(e.values()) <= BF16_TOL, e
+    # the low-rank term must be there: without it the output differs by more than the tolerance
+    y0 = mx.mx_lora_linear_fwd(c["x"], c["W"], bias, c["A"], np.zeros_like(c["B"]), s)
+    assert relerr(y0, yo) > 4 * BF16_TOL

@@ -206,7 +206,7 @@ def test_lora_linear_equals_the_exact_layer_on_representable_data():
 def test_lora_linear_noise_budget_and_reductions():
     from oracle import slora_oracle as so
     from paper_2407_00952_amd import synth
-    c = synth.make_single_layer(T=128, n_in=256, n_out=128, r=4)
+    c = synth.make_single_layer(T=128, n_in=256, n_out=128, r=4, quant=True, bias=True)
     s = c["alpha"] / c["r"]
     y = mx.mx_lora_linear_fwd(c["x"], c["W"], c["b"], c["A"], c["B"], s)
     y_ref, _ = so.lora_linear_fwd(c["x"], c["W"], c["b"], c["A"], c["B"], s)
