@@ -119,8 +119,33 @@ def mxfp8_leg(cfg, stream):
         ms_mx += t_mx
         ms_bf += t_bf
         del x, W, xq, xs, wq, ws, y
+    # the whole compressed LoRA layer (conversion of the activations, rank-space branch, fp8 product with the
+    # bf16 low-rank tail; backward with the adapter gradients) on the qkv-sized and the FC-sized projection
+    layer = []
+    for name, K, N in (("q (d -> d)", d, d), ("fc (d -> d_ff)", d, dff)):
+        r, alpha = cfg.lora_r, cfg.lora_alpha
+        x = torch.randn((T, K), device="cuda", generator=g).to(torch.bfloat16)
+        dyv = torch.randn((T, N), device="cuda", generator=g).to(torch.bfloat16)
+        W = (torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        A = torch.randn((r, K), device="cuda", generator=g) * 0.02
+        Bm = torch.randn((N, r), device="cuda", generator=g) * 0.02
+        nw, nws = B.slora_mx_weight_bytes(K, N), B.slora_mx_lora_linear_ws_bytes(T, K, N, r)
+        packed = torch.empty(nw, dtype=torch.uint8, device="cuda")
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+        y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+        dx = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+        dA = torch.empty((r, K), dtype=torch.float32, device="cuda")
+        dB = torch.empty((N, r), dtype=torch.float32, device="cuda")
+        B.slora_mx_pack_weight(K, N, W, packed, nw, stream)
+        t_f = timed(lambda: B.slora_mx_lora_linear_fwd(T, K, N, r, alpha, x, packed, None, A, Bm, y, ws, nws, stream))
+        t_b = timed(lambda: B.slora_mx_lora_linear_bwd(T, K, N, r, alpha, x, dyv, packed, A, Bm, dx, dA, dB, ws, nws,
+                                                       stream))
+        f = 2.0 * T * K * N
+        layer.append({"name": name, "fwd_us": t_f * 1e3, "bwd_us": t_b * 1e3,
+                      "fwd_tflops": f / (t_f * 1e-3) / 1e12, "bwd_tflops": f / (t_b * 1e-3) / 1e12})
+        del x, dyv, W, packed, ws, y, dx
     ach = flop / (ms_mx * 1e-3) / 1e12
-    return {"what": "y = deq(x) deq(W)^T, MXFP8 operands (E4M3 + E8M0 per 32), bf16 out, T=%d" % T,
+    return {"lora_layer": layer, "what": "y = deq(x) deq(W)^T, MXFP8 operands (E4M3 + E8M0 per 32), bf16 out, T=%d" % T,
             "shapes": shapes, "tflops": ach, "peak": PEAK_FP8_TFLOPS, "frac": ach / PEAK_FP8_TFLOPS,
             "speedup_over_bf16_kernel": ms_bf / ms_mx, "quantize_activation": quant}
 
