@@ -135,3 +135,17 @@ def mx_lora_linear_bwd(x, dy, W, A, B, s):
     dA = s * (dy @ B).T @ x
     dB = s * dy.T @ (x @ A.T)
     return dx, dA, dB
+
+
+def bf16_round(x):
+    """nearest bfloat16 (8 significant bits), ties to even, of float64 values in bf16's normal range"""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                       # x = m 2^e, |m| in [0.5, 1)
+    return np.ldexp(np.rint(m * 256.0), e - 8)
+
+
+def cut_compress(t):
+    """What crosses the cut in compressed form (activations of step a2, activation gradients of step a4,
+    Sec. III-B): the tensor as it would have been sent, i.e. rounded to bf16, then MXFP8 along the feature
+    axis.  Returns (codes, scales)."""
+    return mx_quantize(bf16_round(t))

@@ -222,3 +222,21 @@ def test_lora_linear_noise_budget_and_reductions():
     Z = np.zeros_like(c["B"])
     np.testing.assert_array_equal(mx.mx_lora_linear_fwd(c["x"], c["W"], c["b"], c["A"], Z, s),
                                   mx.mx_linear(*mx.mx_quantize(c["x"]), *mx.mx_quantize(c["W"]), c["b"]))
+
+
+def test_bf16_round_matches_torch_and_cut_compress_composes():
+    rng = np.random.default_rng(8)
+    x = np.concatenate([rng.normal(0, 1, 5000), rng.normal(0, 1e-3, 5000), rng.normal(0, 1e3, 5000)])
+    # exact ties between neighbouring bf16 values
+    b = torch.from_numpy(x[:2000].astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    ties = b + np.ldexp(1.0, np.frexp(b)[1] - 9)
+    x = np.concatenate([x, ties])
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(mx.bf16_round(x), ref)
+    t = rng.normal(0, 2, (6, 64))
+    q, s = mx.cut_compress(t)
+    q2, s2 = mx.mx_quantize(ref_bf := torch.from_numpy(t).to(torch.bfloat16).to(torch.float64).numpy())
+    np.testing.assert_array_equal(q, q2); np.testing.assert_array_equal(s, s2)
+    # what the receiver sees differs from the tensor by the bf16 rounding plus one element step
+    err = np.abs(mx.mx_dequantize(q, s) - t).max() / np.abs(t).max()
+    assert err < 2.0 ** -4 + 2.0 ** -8
