@@ -233,6 +233,20 @@ int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void
  *                         intermediates; bwd does not need a preceding fwd.
  * n_in and n_out multiples of 128, 1 <= r <= SLORA_MAX_RANK, T * max(n_in, n_out) and n_in * n_out below
  * 2^31.  Errors: SLORA_EINVAL, SLORA_ENOSPC (ws or packed buffer too small), SLORA_EHIP. */
+/* The server's round with compressed cut-layer traffic: what the clients upload in step a2 and what goes
+ * back to them in step a4 (Sec. III-B) is MXFP8 instead of bf16.  slora_server_fwd_mx is slora_server_fwd
+ * with client i's activations given as element codes h_xq_clients[i] (u8 [b_i, S, d], 8-byte aligned) and
+ * scale codes h_xs_clients[i] (u8 [b_i, S, d/32]), blocks along d; they are expanded on the fly by the
+ * first LayerNorm (no bf16 copy is made), so the result equals slora_server_fwd on the dequantised
+ * activations bit for bit.  slora_server_bwd_mx is slora_server_bwd with client i's activation gradient
+ * written as codes and scales of the same shapes: Q(bf16(dx)), i.e. exactly slora_mx_quantize of what
+ * slora_server_bwd would have written.  The two forms can be mixed within a round.  Same errors and state
+ * machine as the bf16 calls; d_model is a multiple of 64 already, hence of 32. */
+int slora_server_fwd_mx(slora_ctx *ctx, int K, const void *const *h_xq_clients, const void *const *h_xs_clients,
+                        const int32_t *h_batch, void *y, void *stream);
+int slora_server_bwd_mx(slora_ctx *ctx, const void *dy, void *const *h_dxq_clients, void *const *h_dxs_clients,
+                        void *stream);
+
 size_t slora_mx_weight_bytes(int32_t n_in, int32_t n_out);
 int slora_mx_pack_weight(int32_t n_in, int32_t n_out, const void *W, void *packed, size_t bytes, void *stream);
 size_t slora_mx_lora_linear_ws_bytes(int32_t T, int32_t n_in, int32_t n_out, int32_t r);

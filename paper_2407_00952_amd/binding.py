@@ -30,7 +30,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_loss_head_prepare", "slora_loss_head", "slora_client_fwd", "slora_client_bwd",
            "slora_adapters_changed", "slora_adamw", "slora_mx_quantize", "slora_mx_dequantize",
            "slora_frozen_linear_mxfp8", "slora_mx_weight_bytes", "slora_mx_pack_weight",
-           "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd"]
+           "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd",
+           "slora_server_fwd_mx", "slora_server_bwd_mx"]
 
 
 class slora_config(ctypes.Structure):
@@ -85,6 +86,8 @@ def lib():
         L.slora_mx_quantize.argtypes = [i64, i32, vp, i64, vp, vp, vp]
         L.slora_mx_dequantize.argtypes = [i64, i32, vp, vp, vp, i64, vp]
         L.slora_frozen_linear_mxfp8.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.slora_server_fwd_mx.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.slora_server_bwd_mx.argtypes = [vp, vp, vp, vp, vp]
         L.slora_mx_weight_bytes.argtypes = [i32, i32]
         L.slora_mx_weight_bytes.restype = sz
         L.slora_mx_pack_weight.argtypes = [i32, i32, vp, vp, sz, vp]
@@ -169,6 +172,17 @@ def slora_server_fwd(ctx, x_clients, batch, y, stream=None):
 
 def slora_server_bwd(ctx, dy, dx_clients, stream=None):
     _check(lib().slora_server_bwd(ctx, _p(dy), _ptr_array(dx_clients), _stream(stream)))
+
+
+def slora_server_fwd_mx(ctx, xq_clients, xs_clients, batch, y, stream=None):
+    K = len(xq_clients)
+    b = (ctypes.c_int32 * K)(*[int(v) for v in batch])
+    _check(lib().slora_server_fwd_mx(ctx, K, _ptr_array(xq_clients), _ptr_array(xs_clients), b, _p(y),
+                                     _stream(stream)))
+
+
+def slora_server_bwd_mx(ctx, dy, dxq_clients, dxs_clients, stream=None):
+    _check(lib().slora_server_bwd_mx(ctx, _p(dy), _ptr_array(dxq_clients), _ptr_array(dxs_clients), _stream(stream)))
 
 
 def slora_adapter_step(ctx, lr, stream=None):
@@ -344,6 +358,12 @@ class Server:
 
     def bwd(self, dy, dx_clients, stream=None):
         slora_server_bwd(self.ctx, dy, dx_clients, stream)
+
+    def fwd_mx(self, xq_clients, xs_clients, y, stream=None):
+        slora_server_fwd_mx(self.ctx, xq_clients, xs_clients, [t.shape[0] for t in xq_clients], y, stream)
+
+    def bwd_mx(self, dy, dxq_clients, dxs_clients, stream=None):
+        slora_server_bwd_mx(self.ctx, dy, dxq_clients, dxs_clients, stream)
 
     def step(self, lr, stream=None):
         slora_adapter_step(self.ctx, lr, stream)

@@ -482,8 +482,9 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
     return SLORA_OK;
 }
 
-int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const int32_t *h_batch, void *y,
-                     void *stream)
+// shared by the bf16 and the compressed form of the server forward: `h_scales` null = bf16 client buffers
+static int server_fwd_common(slora_ctx *c, int K, const void *const *h_x_clients, const void *const *h_scales,
+                             const int32_t *h_batch, void *y, void *stream)
 {
     if (!c || !h_x_clients || !h_batch || !y) return SLORA_EINVAL;
     if (K <= 0 || K > SLORA_MAX_CLIENTS) return SLORA_EINVAL;
@@ -491,6 +492,7 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
     for (int i = 0; i < K; ++i) {
         if (!h_x_clients[i] || h_batch[i] <= 0) return SLORA_EINVAL;
         if (((uintptr_t)h_x_clients[i]) & 7) return SLORA_EINVAL;
+        if (h_scales && !h_scales[i]) return SLORA_EINVAL;
         nseq += h_batch[i];
     }
     if (nseq > c->cfg.max_seqs) return SLORA_EINVAL;
@@ -500,14 +502,29 @@ int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const 
     c->K = K; c->n_seq = (int)nseq; c->T = c->n_seq * c->S;
     ClientTable tab;
     tab.K = K;
+    tab.mx = h_scales ? 1 : 0;
     int rows = 0;
     for (int i = 0; i < K; ++i) {
         rows += h_batch[i] * c->S;
         tab.ptr[i] = (void *)h_x_clients[i];
+        tab.aux[i] = h_scales ? (void *)h_scales[i] : nullptr;
         tab.row_end[i] = rows;
         c->row_end[i] = rows;
     }
     return stack_fwd(c, &tab, nullptr, y, (hipStream_t)stream);
+}
+
+int slora_server_fwd(slora_ctx *c, int K, const void *const *h_x_clients, const int32_t *h_batch, void *y,
+                     void *stream)
+{
+    return server_fwd_common(c, K, h_x_clients, nullptr, h_batch, y, stream);
+}
+
+int slora_server_fwd_mx(slora_ctx *c, int K, const void *const *h_xq_clients, const void *const *h_xs_clients,
+                        const int32_t *h_batch, void *y, void *stream)
+{
+    if (!h_xs_clients) return SLORA_EINVAL;
+    return server_fwd_common(c, K, h_xq_clients, h_xs_clients, h_batch, y, stream);
 }
 
 int slora_client_fwd(slora_ctx *c, int32_t batch, const int32_t *tokens, int32_t vocab, const void *wte,
@@ -640,17 +657,37 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
     return SLORA_OK;
 }
 
-int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, void *stream)
+static int server_bwd_common(slora_ctx *c, const void *dy, void *const *h_dx_clients, void *const *h_scales,
+                             void *stream)
 {
     if (!c || !dy || !h_dx_clients) return SLORA_EINVAL;
     if (c->state != 1) return SLORA_ESTATE;
-    for (int i = 0; i < c->K; ++i)
+    for (int i = 0; i < c->K; ++i) {
         if (!h_dx_clients[i] || (((uintptr_t)h_dx_clients[i]) & 7)) return SLORA_EINVAL;
+        if (h_scales && !h_scales[i]) return SLORA_EINVAL;
+    }
     if (((uintptr_t)dy) & 15) return SLORA_EINVAL;
     ClientTable tab;
     tab.K = c->K;
-    for (int i = 0; i < c->K; ++i) { tab.ptr[i] = h_dx_clients[i]; tab.row_end[i] = c->row_end[i]; }
+    tab.mx = h_scales ? 1 : 0;
+    for (int i = 0; i < c->K; ++i) {
+        tab.ptr[i] = h_dx_clients[i];
+        tab.aux[i] = h_scales ? h_scales[i] : nullptr;
+        tab.row_end[i] = c->row_end[i];
+    }
     return stack_bwd(c, dy, &tab, (hipStream_t)stream);
+}
+
+int slora_server_bwd(slora_ctx *c, const void *dy, void *const *h_dx_clients, void *stream)
+{
+    return server_bwd_common(c, dy, h_dx_clients, nullptr, stream);
+}
+
+int slora_server_bwd_mx(slora_ctx *c, const void *dy, void *const *h_dxq_clients, void *const *h_dxs_clients,
+                        void *stream)
+{
+    if (!h_dxs_clients) return SLORA_EINVAL;
+    return server_bwd_common(c, dy, h_dxq_clients, h_dxs_clients, stream);
 }
 
 int slora_client_bwd(slora_ctx *c, const void *dact, void *stream)

@@ -46,9 +46,11 @@ static __device__ __forceinline__ void gelu_fwd_bwd(float f, float &gval, float 
 
 // The K clients' buffers as one logical [sum b_i * S, d] matrix (client-major concatenation).
 struct ClientTable {
-    void *ptr[SL_MAX_CLIENTS];
+    void *ptr[SL_MAX_CLIENTS];     // bf16 rows, or MXFP8 element codes when mx != 0
+    void *aux[SL_MAX_CLIENTS];     // MXFP8 scale codes ([rows, d/32]) when mx != 0, unused otherwise
     int row_end[SL_MAX_CLIENTS];   // exclusive prefix of rows (tokens)
     int K;
+    int mx;                        // the buffers hold MXFP8 (compressed cut-layer traffic) instead of bf16
 };
 
 // Token + position embedding as the source of the first client-side block (row t of the input is

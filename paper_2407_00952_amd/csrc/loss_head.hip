@@ -240,6 +240,7 @@ int slora_loss_head(int32_t T, int32_t d_model, int32_t vocab, const void *y, co
     int rc;
 
     ClientTable one;                      // the stack output as a single "client" buffer of bf16 rows
+    one.mx = 0;
     one.K = 1;
     one.ptr[0] = const_cast<void *>(y);
     one.row_end[0] = T;

@@ -19,6 +19,7 @@
 // rows 4g + e.
 #include "../../include/slora.h"
 #include "common.h"
+#include "mx_codec.h"
 
 namespace {
 
@@ -28,17 +29,6 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 // ------------------------------------------------------------------------------------------------
 // conversion kernels
 // ------------------------------------------------------------------------------------------------
-
-// E4M3 code of a non-negative fp32 value below 512: round to nearest, ties to even, clamp at 448.
-__device__ __forceinline__ unsigned e4m3_from_f32(float a)
-{
-    a = fminf(a, 448.0f);
-    if (a < 0.015625f)                                   // below the smallest normal 2^-6: multiples of 2^-9
-        return (unsigned)__builtin_rintf(a * 512.0f);    // 8 is the code of 2^-6 itself
-    unsigned b = __float_as_uint(a);
-    b += 0x7FFFFu + ((b >> 20) & 1u);                    // ties to even on the 3 kept mantissa bits
-    return (b >> 20) - ((127u - 7u) << 3);               // rebias the exponent
-}
 
 // Each thread converts 8 consecutive elements of a row; 4 neighbouring threads form a block of 32.
 __global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict__ x, long long ldx, long long M, int K,
@@ -62,29 +52,17 @@ __global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict
     }
     mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
     mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
-    // shared exponent: floor(log2 max) - 8, i.e. scale code = biased exponent - 8, held at 0
-    const int E = (int)(mag >> 7);
-    const int scode = max(E - 8, 0);
+    const int scode = mx_scale_code(mag);
     unsigned out[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const unsigned h = (i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu);
-        const float v = __uint_as_float((h & 0x7FFFu) << 16);
-        const float sc = ldexpf(v, 127 - scode);         // exact: division by the block scale
-        const unsigned c = e4m3_from_f32(sc) | ((h >> 8) & 0x80u);
-        out[i >> 2] |= c << (8 * (i & 3));
+        out[i >> 2] |= mx_encode_bf16(h, scode) << (8 * (i & 3));
     }
     if (live) {
         *(uint2 *)(codes + row * (long long)K + ch * 8) = make_uint2(out[0], out[1]);
         if ((ch & 3) == 0) scales[row * (long long)(K >> 5) + (ch >> 2)] = (unsigned char)scode;
     }
-}
-
-__device__ __forceinline__ float e4m3_to_f32(unsigned c)
-{
-    const unsigned e = (c >> 3) & 15u, m = c & 7u;
-    const float mag = e ? __uint_as_float(((e + 120u) << 23) | (m << 20)) : (float)m * 0.001953125f;
-    return (c & 0x80u) ? -mag : mag;
 }
 
 __global__ __launch_bounds__(256) void mx_dequantize_kernel(const unsigned char *__restrict__ codes,
@@ -102,7 +80,7 @@ __global__ __launch_bounds__(256) void mx_dequantize_kernel(const unsigned char 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const unsigned c = ((i < 4 ? raw.x : raw.y) >> (8 * (i & 3))) & 0xFFu;
-        o[i] = f2bf(ldexpf(e4m3_to_f32(c), scode - 127));
+        o[i] = f2bf(ldexpf(mx_e4m3_to_f32(c), scode - 127));
     }
     *(bf16x8 *)(y + row * ldy + ch * 8) = o;
 }

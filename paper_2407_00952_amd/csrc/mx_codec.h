@@ -1,0 +1,34 @@
+// MXFP8 element / scale codec shared by the conversion kernels and by the kernels that read or write
+// compressed cut-layer buffers (OCP Microscaling Formats v1.0: FP8 E4M3 elements, bias 7, largest finite
+// value 448, S.1111.111 = NaN; E8M0 block scale = 2^(code - 127); conversion per Sec. 6.3 of that document).
+#pragma once
+#include <hip/hip_runtime.h>
+
+// E4M3 code of a non-negative fp32 value below 512: round to nearest, ties to even, clamp at 448.
+static __device__ __forceinline__ unsigned mx_e4m3_from_f32(float a)
+{
+    a = fminf(a, 448.0f);
+    if (a < 0.015625f)                                   // below the smallest normal 2^-6: multiples of 2^-9
+        return (unsigned)__builtin_rintf(a * 512.0f);    // 8 is the code of 2^-6 itself
+    unsigned b = __float_as_uint(a);
+    b += 0x7FFFFu + ((b >> 20) & 1u);                    // ties to even on the 3 kept mantissa bits
+    return (b >> 20) - ((127u - 7u) << 3);               // rebias the exponent
+}
+
+static __device__ __forceinline__ float mx_e4m3_to_f32(unsigned c)
+{
+    const unsigned e = (c >> 3) & 15u, m = c & 7u;
+    const float mag = e ? __uint_as_float(((e + 120u) << 23) | (m << 20)) : (float)m * 0.001953125f;
+    return (c & 0x80u) ? -mag : mag;
+}
+
+// scale code of a block from the bf16 bit pattern of its largest magnitude (sign bit cleared):
+// floor(log2 max) - 8, i.e. biased exponent - 8, held at 0 (which also covers the zero block)
+static __device__ __forceinline__ int mx_scale_code(unsigned max_mag_bf16_bits) { return max((int)(max_mag_bf16_bits >> 7) - 8, 0); }
+
+// element code of one bf16 value (bit pattern h) under the block's scale code
+static __device__ __forceinline__ unsigned mx_encode_bf16(unsigned h, int scode)
+{
+    const float v = __uint_as_float((h & 0x7FFFu) << 16);
+    return mx_e4m3_from_f32(ldexpf(v, 127 - scode)) | ((h >> 8) & 0x80u);   // exact division by the scale
+}

@@ -13,6 +13,7 @@
 //             written as fp32 (residual gradient) and/or bf16 (next GEMM operand, or the
 //             per-client activation gradient scattered back to the K client buffers).
 #include "common.h"
+#include "mx_codec.h"
 
 namespace {
 
@@ -26,7 +27,8 @@ __device__ __forceinline__ int client_of(const ClientTable &t, int row, int &loc
     return c;
 }
 
-// SRC 0: fp32 rows of h; 1: bf16 rows gathered from the client buffers; 2: embedding lookup
+// SRC 0: fp32 rows of h; 1: bf16 rows gathered from the client buffers; 2: embedding lookup;
+// 3: MXFP8 rows (element codes + one scale code per 32 columns) gathered from the client buffers
 template <int SRC>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h, ClientTable tab, EmbedSrc emb,
                                                      float *__restrict__ hcopy, const bf16 *__restrict__ gamma,
@@ -39,7 +41,13 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
     if (row >= T) return;
     float v[MAXC][4];
     const bf16 *src16 = nullptr, *pos16 = nullptr;
-    if (SRC == 1) {
+    const unsigned char *srcq = nullptr, *srcs = nullptr;
+    if (SRC == 3) {
+        int local;
+        int c = client_of(tab, row, local);
+        srcq = (const unsigned char *)tab.ptr[c] + (size_t)local * d;
+        srcs = (const unsigned char *)tab.aux[c] + (size_t)local * (d >> 5);
+    } else if (SRC == 1) {
         int local;
         int c = client_of(tab, row, local);
         src16 = (const bf16 *)tab.ptr[c] + (size_t)local * d;
@@ -53,7 +61,13 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
     for (int c = 0; c < MAXC; ++c) {
         const int col = c * 256 + lane * 4;
         if (col < d) {
-            if (GATHER) {
+            if (SRC == 3) {
+                const unsigned q4 = *(const unsigned *)(srcq + col);
+                const int sc = (int)srcs[col >> 5] - 127;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[c][i] = ldexpf(mx_e4m3_to_f32((q4 >> (8 * i)) & 0xFFu), sc);
+                *(float4 *)(hcopy + (size_t)row * d + col) = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
+            } else if (GATHER) {
                 bf16x4 t = *(const bf16x4 *)(src16 + col);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[c][i] = bf2f(t[i]);
@@ -98,8 +112,9 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
 
 // DRES16: the residual gradient arrives as bf16 (last block: the caller's dY) instead of fp32;
 // with DRES16 false a null `dres` means there is no residual gradient to add.
-// SCATTER: the bf16 output goes to the K client buffers.
-template <bool DRES16, bool SCATTER>
+// SCATTER 1: the bf16 output goes to the K client buffers; 2: it goes there as MXFP8 (the value is rounded
+// to bf16 first, then converted block by block: 8 neighbouring lanes hold one block of 32 columns).
+template <bool DRES16, int SCATTER>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du, const float *__restrict__ h,
                                                      const float *__restrict__ stats, const bf16 *__restrict__ gamma,
                                                      const void *__restrict__ dres, float *__restrict__ out32,
@@ -131,14 +146,22 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du
     const float m1 = wave_sum(s1) / (float)d;
     const float m2 = wave_sum(s2) / (float)d;
     bf16 *dst16 = out16 ? out16 + (size_t)row * d : nullptr;
+    unsigned char *dstq = nullptr, *dsts = nullptr;
     if (SCATTER) {
         int local;
         int c = client_of(tab, row, local);
-        dst16 = (bf16 *)tab.ptr[c] + (size_t)local * d;
+        if (SCATTER == 2) {
+            dstq = (unsigned char *)tab.ptr[c] + (size_t)local * d;
+            dsts = (unsigned char *)tab.aux[c] + (size_t)local * (d >> 5);
+            dst16 = nullptr;
+        } else {
+            dst16 = (bf16 *)tab.ptr[c] + (size_t)local * d;
+        }
     }
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int col = c * 256 + lane * 4;
+        float r_keep[4] = {0.f, 0.f, 0.f, 0.f};
         if (col < d) {
             float r[4];
             if (DRES16) {
@@ -156,9 +179,33 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du
             for (int i = 0; i < 4; ++i) {
                 r[i] += rho * (gq[c][i] - m1 - xh[c][i] * m2);
                 o16[i] = f2bf(r[i]);
+                r_keep[i] = r[i];
             }
             if (out32) *(float4 *)(out32 + (size_t)row * d + col) = make_float4(r[0], r[1], r[2], r[3]);
             if (dst16) *(bf16x4 *)(dst16 + col) = o16;
+        }
+        if (SCATTER == 2) {
+            // every lane of the wave takes part in the shuffles; d is a multiple of 32, so the 8 lanes of a
+            // block are either all inside the row or all outside
+            unsigned hb[4] = {0u, 0u, 0u, 0u}, mag = 0u;
+            if (col < d) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    hb[i] = (unsigned)__builtin_bit_cast(unsigned short, f2bf(r_keep[i]));
+                    mag = max(mag, hb[i] & 0x7FFFu);
+                }
+            }
+            mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
+            mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
+            mag = max(mag, (unsigned)__shfl_xor((int)mag, 4, 64));
+            const int scode = mx_scale_code(mag);
+            if (col < d) {
+                unsigned q4 = 0u;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) q4 |= mx_encode_bf16(hb[i], scode) << (8 * i);
+                *(unsigned *)(dstq + col) = q4;
+                if ((lane & 7) == 0) dsts[col >> 5] = (unsigned char)scode;
+            }
         }
     }
 }
@@ -170,14 +217,19 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, 
                   const EmbedSrc *embed)
 {
     if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
+    if (gather && gather->mx && (d % 32)) return -1;
     dim3 grid((T + 3) / 4), block(256);
     ClientTable none;
     none.K = 0;
+    none.mx = 0;
     EmbedSrc noemb = {nullptr, nullptr, nullptr, 1, 1};
     if (embed) {
         if (!embed->tokens || !embed->wte || !embed->wpe || embed->seq_len <= 0 || embed->vocab <= 0) return -1;
         hipLaunchKernelGGL((ln_fwd_kernel<2>), grid, block, 0, st, nullptr, none, *embed, h_copy, gamma, beta, eps, u,
                            stats, T, d);
+    } else if (gather && gather->mx) {
+        hipLaunchKernelGGL((ln_fwd_kernel<3>), grid, block, 0, st, nullptr, *gather, noemb, h_copy, gamma, beta, eps,
+                           u, stats, T, d);
     } else if (gather) {
         hipLaunchKernelGGL((ln_fwd_kernel<1>), grid, block, 0, st, nullptr, *gather, noemb, h_copy, gamma, beta, eps,
                            u, stats, T, d);
@@ -197,20 +249,26 @@ int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16
     dim3 grid((T + 3) / 4), block(256);
     ClientTable tab;
     tab.K = 0;
+    tab.mx = 0;
     if (scatter) tab = *scatter;
-    if (dres_bf16) {
+    if (scatter && scatter->mx) {
+        // compressed activation gradients: only the first server block scatters, and its residual gradient is fp32
+        if ((d % 32) || dres_bf16) return -1;
+        hipLaunchKernelGGL((ln_bwd_kernel<false, 2>), grid, block, 0, st, du, h, stats, gamma, (const void *)dres_f32,
+                           out_f32, out_bf16, tab, T, d);
+    } else if (dres_bf16) {
         if (scatter)
-            hipLaunchKernelGGL((ln_bwd_kernel<true, true>), grid, block, 0, st, du, h, stats, gamma,
+            hipLaunchKernelGGL((ln_bwd_kernel<true, 1>), grid, block, 0, st, du, h, stats, gamma,
                                (const void *)dres_bf16, out_f32, out_bf16, tab, T, d);
         else
-            hipLaunchKernelGGL((ln_bwd_kernel<true, false>), grid, block, 0, st, du, h, stats, gamma,
+            hipLaunchKernelGGL((ln_bwd_kernel<true, 0>), grid, block, 0, st, du, h, stats, gamma,
                                (const void *)dres_bf16, out_f32, out_bf16, tab, T, d);
     } else {
         if (scatter)
-            hipLaunchKernelGGL((ln_bwd_kernel<false, true>), grid, block, 0, st, du, h, stats, gamma,
+            hipLaunchKernelGGL((ln_bwd_kernel<false, 1>), grid, block, 0, st, du, h, stats, gamma,
                                (const void *)dres_f32, out_f32, out_bf16, tab, T, d);
         else
-            hipLaunchKernelGGL((ln_bwd_kernel<false, false>), grid, block, 0, st, du, h, stats, gamma,
+            hipLaunchKernelGGL((ln_bwd_kernel<false, 0>), grid, block, 0, st, du, h, stats, gamma,
                                (const void *)dres_f32, out_f32, out_bf16, tab, T, d);
     }
     SL_CHECK_LAUNCH("ln_bwd");

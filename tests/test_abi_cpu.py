@@ -172,6 +172,9 @@ def test_mx_argument_checks():
     assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok, None, ok, ok, None, ok, None) == B.SLORA_EINVAL
     assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok + 8, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL
     assert L.slora_frozen_linear_mxfp8(1 << 22, 1024, 8, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL   # 2^32 bytes
+    # compressed cut-layer traffic: the same checks as the bf16 calls plus the scale tables
+    assert L.slora_server_fwd_mx(None, 1, ok, ok, ok, ok, None) == B.SLORA_EINVAL
+    assert L.slora_server_bwd_mx(None, ok, ok, ok, None) == B.SLORA_EINVAL
     # the compressed LoRA layer
     assert L.slora_mx_weight_bytes(100, 128) == 0 and L.slora_mx_weight_bytes(128, 256) > 128 * 256 * 2
     assert L.slora_mx_lora_linear_ws_bytes(64, 128, 128, 17) == 0 and L.slora_mx_lora_linear_ws_bytes(64, 128, 128, 4) > 0

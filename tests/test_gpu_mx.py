@@ -231,3 +231,70 @@ def test_lora_linear_mxfp8(T, n_in, n_out, r, with_bias):
     # the low-rank term must be there: without it the output differs by more than the tolerance
     y0 = mx.mx_lora_linear_fwd(c["x"], c["W"], bias, c["A"], np.zeros_like(c["B"]), s)
     assert relerr(y0, yo) > 4 * BF16_TOL
+
+
+def test_server_round_with_compressed_cut_traffic():
+    """slora_server_fwd_mx / slora_server_bwd_mx: the clients' activations arrive as MXFP8 and their gradients
+    leave as MXFP8 (Sec. III-B a2, a4 with the compression of Sec. V-B)."""
+    import torch
+    from gpu_util import oracle_of
+    cfg = synth.tiny_config(d_model=320, n_head=5, d_ff=704, n_blocks=2, lora_r=4, lora_proj=("q", "v"),
+                            n_clients=3, batch=2, seq_len=128, seed=synth.BASE_SEED + 77)
+    inp = synth.make_stack_inputs(cfg)
+    say("compressed cut traffic", cfg.d_model, cfg.n_blocks)
+    # ragged client batches: 1, 2 and 3 sequences
+    clients = [inp["clients"][0][:1], inp["clients"][1][:2], np.concatenate([inp["clients"][2], inp["clients"][0][:1]])]
+    n_seq = sum(c.shape[0] for c in clients)
+    dY = inp["dY"][:n_seq]
+    S, d = cfg.seq_len, cfg.d_model
+    # what the clients send: the oracle's compression of their activations
+    sent = [mx.cut_compress(c) for c in clients]
+    received = [mx.mx_dequantize(q, s).astype(np.float32) for q, s in sent]
+    srv = B.Server(cfg, inp["blocks"], inp["adapters"], max_seqs=n_seq)
+    t8 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    xq = [t8(q) for q, _ in sent]; xs = [t8(s) for _, s in sent]
+    y = torch.empty((n_seq, S, d), dtype=torch.bfloat16, device="cuda")
+    dy = B.to_device_bf16(dY)
+    dxq = [torch.zeros_like(t) for t in xq]; dxs = [torch.zeros_like(t) for t in xs]
+    srv.fwd_mx(xq, xs, y)
+    srv.bwd_mx(dy, dxq, dxs)
+    torch.cuda.synchronize()
+    grads = [{p: (t[2].cpu().numpy().copy(), t[3].cpu().numpy().copy()) for p, t in ad.items()} for ad in srv.adapters]
+    Y = B.from_device_bf16(y)
+    # (1) the uncompressed calls on the dequantised activations give the same bits, and the codes written are
+    #     the conversion (by the oracle) of the bf16 gradients those calls write
+    x16 = [B.to_device_bf16(r) for r in received]
+    y2 = torch.empty_like(y); dx16 = [torch.empty_like(t) for t in x16]
+    srv.fwd(x16, y2); srv.bwd(dy, dx16)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    for i in range(len(clients)):
+        q, s = mx.mx_quantize(B.from_device_bf16(dx16[i]))
+        np.testing.assert_array_equal(dxq[i].cpu().numpy(), q)
+        np.testing.assert_array_equal(dxs[i].cpu().numpy(), s)
+    # (2) against the oracle: forward on what was received, backward, compression of the gradients
+    orc = oracle_of(cfg, inp)
+    Yo = orc.fwd([r.astype(np.float64) for r in received])
+    dXo = orc.bwd(dY)
+    e = {"Y": relerr(Y, Yo)}
+    for i in range(len(clients)):
+        qo, so_ = mx.cut_compress(dXo[i])
+        got = mx.mx_dequantize(dxq[i].cpu().numpy(), dxs[i].cpu().numpy())
+        e["dx%d" % i] = relerr(got, mx.mx_dequantize(qo, so_))
+        # the codes themselves agree wherever the two bf16 gradients do: count the disagreements
+        e["codes%d_differ" % i] = float((dxq[i].cpu().numpy() != qo).mean())
+    for l, gl in enumerate(orc.grads):
+        for p, (dA, dB) in gl.items():
+            e["dA[%d,%s]" % (l, p)] = relerr(grads[l][p][0], dA)
+            e["dB[%d,%s]" % (l, p)] = relerr(grads[l][p][1], dB)
+    say("   " + ", ".join("%s=%.2e" % kv for kv in e.items()))
+    # Y and the adapter gradients: the stack's bf16 bound.  The compressed gradients: both sides quantise a
+    # bf16 tensor, the two tensors differ by at most BF16_TOL, and a value near a rounding boundary may then
+    # land on the neighbouring code, one element step (2^-4 of the block maximum at most) away.
+    for k, v in e.items():
+        if k.startswith("codes"):
+            assert v < 0.2, (k, v)
+        elif k.startswith("dx"):
+            assert v <= BF16_TOL + 2.0 ** -4, (k, v)
+        else:
+            assert v <= BF16_TOL, (k, v)
