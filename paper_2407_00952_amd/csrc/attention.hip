@@ -526,75 +526,86 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
         if (wave < 4) AT_GLDS(base + (size_t)row_c * ld + lch_c * 8, (Qd) + (wave & 3) * 1024);        \
         else AT_GLDS(dbase + (size_t)row_c * d + lch_c * 8, (Dd) + (wave & 3) * 1024);                 \
     }
-    // phase 1 for query tile `it` (rows 32 it ..) against this wave's blocks that it can see
+    // phase 1 for query tile `it` (rows 32 it ..) against this wave's blocks that it can see.  Only the
+    // block on the diagonal (j == it) needs the causal mask; the blocks below it run a copy without it.
+#define FB_BLOCK(Qs, Ds, dSw, it, b, j, DIAG)                                                          \
+    {                                                                                                  \
+        f32x16 sacc = zero16(), dpacc = zero16();                                                      \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                             \
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Qs, r32, ks, g),                    \
+                                                            frag_rm(Ks, 32 * (j) + r32, ks, g), sacc, 0, 0, 0); \
+            dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ds, r32, ks, g), vf[b][ks],        \
+                                                             dpacc, 0, 0, 0);                          \
+        }                                                                                              \
+        _Pragma("unroll") for (int e4 = 0; e4 < 4; ++e4) {                                             \
+            const int ql = 8 * e4 + 4 * g;                                                             \
+            const f32x4 ls = *(const f32x4 *)(lse_s + 32 * (it) + ql);                                 \
+            const f32x4 dd = *(const f32x4 *)(dl_s + 32 * (it) + ql);                                  \
+            bf16x4 dst4;                                                                               \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                            \
+                const int e = 4 * e4 + i;                                                              \
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i]));                   \
+                if (DIAG && r32 > ql + i) p = 0.f;                                                     \
+                sacc[e] = p;                                                                           \
+                dpacc[e] = p * (dpacc[e] - dd[i]);                                                     \
+                dst4[i] = f2bf(dpacc[e]);                                                              \
+            }                                                                                          \
+            const int key = 32 * (j) + r32;                                                            \
+            *(bf16x4 *)((dSw) + key * 64 + (((2 * e4 + g) ^ dsm(key)) << 3)) = dst4;                   \
+        }                                                                                              \
+        _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                             \
+            bf16x8 pb, dsb;                                                                            \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                            \
+                pb[i] = f2bf(sacc[8 * hh + i]);                                                        \
+                dsb[i] = f2bf(dpacc[8 * hh + i]);                                                      \
+            }                                                                                          \
+            _Pragma("unroll") for (int dt = 0; dt < 2; ++dt) {                                         \
+                dvacc[b][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                \
+                    frag_tr(Ds, 32 * dt, 16 * hh, lane), pb, dvacc[b][dt], 0, 0, 0);                   \
+                dkacc[b][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                \
+                    frag_tr(Qs, 32 * dt, 16 * hh, lane), dsb, dkacc[b][dt], 0, 0, 0);                  \
+            }                                                                                          \
+        }                                                                                              \
+    }
 #define FB_PHASE1(Qs, Ds, dSw, it)                                                                     \
     if (owner) {                                                                                       \
         _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                \
             const int j = jb[b];                                                                       \
-            if (j <= (it)) {                                                                           \
-                const bool diag = j == (it);                                                           \
-                f32x16 sacc = zero16(), dpacc = zero16();                                              \
-                _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                     \
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Qs, r32, ks, g),            \
-                                                                    frag_rm(Ks, 32 * j + r32, ks, g), sacc, 0, 0, 0); \
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ds, r32, ks, g), vf[b][ks], \
-                                                                     dpacc, 0, 0, 0);                  \
-                }                                                                                      \
-                _Pragma("unroll") for (int e4 = 0; e4 < 4; ++e4) {                                     \
-                    const int ql = 8 * e4 + 4 * g;                                                     \
-                    const f32x4 ls = *(const f32x4 *)(lse_s + 32 * (it) + ql);                         \
-                    const f32x4 dd = *(const f32x4 *)(dl_s + 32 * (it) + ql);                          \
-                    bf16x4 dst4;                                                                       \
-                    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                    \
-                        const int e = 4 * e4 + i;                                                      \
-                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], kScaleLog2, -ls[i]));           \
-                        if (diag && r32 > ql + i) p = 0.f;                                             \
-                        sacc[e] = p;                                                                   \
-                        dpacc[e] = p * (dpacc[e] - dd[i]);                                             \
-                        dst4[i] = f2bf(dpacc[e]);                                                      \
-                    }                                                                                  \
-                    const int key = 32 * j + r32;                                                      \
-                    *(bf16x4 *)((dSw) + key * 64 + (((2 * e4 + g) ^ dsm(key)) << 3)) = dst4;           \
-                }                                                                                      \
-                _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                     \
-                    bf16x8 pb, dsb;                                                                    \
-                    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                    \
-                        pb[i] = f2bf(sacc[8 * hh + i]);                                                \
-                        dsb[i] = f2bf(dpacc[8 * hh + i]);                                              \
-                    }                                                                                  \
-                    _Pragma("unroll") for (int dt = 0; dt < 2; ++dt) {                                 \
-                        dvacc[b][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
-                            frag_tr(Ds, 32 * dt, 16 * hh, lane), pb, dvacc[b][dt], 0, 0, 0);           \
-                        dkacc[b][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
-                            frag_tr(Qs, 32 * dt, 16 * hh, lane), dsb, dkacc[b][dt], 0, 0, 0);          \
-                    }                                                                                  \
-                }                                                                                      \
-            }                                                                                          \
+            if (j <= (it)) { const bool diag = j == (it); FB_BLOCK(Qs, Ds, dSw, it, b, j, diag) }      \
             __builtin_amdgcn_sched_barrier(0);           /* keep the two blocks' live ranges apart */   \
         }                                                                                              \
     }
     // phase 2 for query tile `it`: wave w forms dQ[16 qt .. +15][16 dt .. +15], qt = w / 4, dt = w % 4,
     // as (K^T dS^T)^T over all visible keys; the lane ends up with 4 consecutive columns of one query
+    // The rows a lane reads are 32 kk + (a lane constant below 32) and neither swizzle looks above bit 3 of
+    // the row, so everything but the 32 kk step is formed once here (left in the loop the compiler rebuilt the
+    // swizzles for every key block: 17 VALU instructions per MFMA).
+    const int p2_qt = wave >> 2, p2_dt = wave & 3;
+    int p2_k[2], p2_d[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = 8 * kg + 4 * h + (i16 >> 2);
+        const int colk = 16 * p2_dt + 4 * (i16 & 3);
+        p2_k[h] = row * 128 + (((colk >> 3) ^ swm(row)) << 4) + (colk & 7) * 2;
+        p2_d[h] = row * 64 + (((4 * p2_qt + (i16 & 3)) ^ dsm(row)) << 3);
+    }
 #define FB_PHASE2(dSr, it)                                                                             \
     {                                                                                                  \
-        const int qt = wave >> 2, dt = wave & 3;                                                       \
         f32x4 qacc = {0.f, 0.f, 0.f, 0.f};                                                             \
         _Pragma("unroll 2") for (int kk = 0; kk <= (it); ++kk) {                                       \
             union { v4s s[2]; bf16x8 v; } ua, ub;                                                      \
             _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                            \
-                const int row = 32 * kk + 8 * kg + 4 * h + (i16 >> 2);                                 \
-                const int colk = 16 * dt + 4 * (i16 & 3);                                              \
-                const unsigned char *pk = Ks + row * 128 + (((colk >> 3) ^ swm(row)) << 4) + (colk & 7) * 2; \
-                const unsigned char *pd = (dSr) + row * 64 + (((4 * qt + (i16 & 3)) ^ dsm(row)) << 3); \
+                const unsigned char *pk = Ks + kk * 4096 + p2_k[h];                                    \
+                const unsigned char *pd = (dSr) + kk * 2048 + p2_d[h];                                 \
                 ua.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)pk); \
                 ub.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)pd); \
             }                                                                                          \
             qacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua.v, ub.v, qacc, 0, 0, 0);                 \
         }                                                                                              \
-        const int q = 32 * (it) + 16 * qt + i16;                                                       \
+        const int q = 32 * (it) + 16 * p2_qt + i16;                                                    \
         bf16x4 w4;                                                                                     \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) w4[e] = f2bf(qacc[e] * 0.125f);                  \
-        *(bf16x4 *)(dqkv + ((size_t)n * S + q) * ld + a * 64 + 16 * dt + 4 * kg) = w4;                 \
+        *(bf16x4 *)(dqkv + ((size_t)n * S + q) * ld + a * 64 + 16 * p2_dt + 4 * kg) = w4;              \
     }
 
     FB_COPY(Qb0, Db0, 0)
@@ -618,6 +629,7 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
     }
 #undef FB_COPY
 #undef FB_PHASE1
+#undef FB_BLOCK
 #undef FB_PHASE2
 
     if (owner) {
