@@ -149,3 +149,81 @@ def cut_compress(t):
     Sec. III-B): the tensor as it would have been sent, i.e. rounded to bf16, then MXFP8 along the feature
     axis.  Returns (codes, scales)."""
     return mx_quantize(bf16_round(t))
+
+
+# ---- MXFP4: FP4 E2M1 elements (1 sign, 2 exponent bits with bias 1, 1 mantissa bit; no NaN, no Inf;
+#      values 0, 0.5, 1, 1.5, 2, 3, 4, 6) under the same E8M0 block scale; emax_elem = 2 (MX v1.0 Sec. 5.3.3, 6.3).
+#      Used for the frozen weights only (4.25 bits per weight).
+
+def _e2m1_table():
+    t = np.empty(16, dtype=np.float64)
+    for c in range(16):
+        s, e, m = c >> 3, (c >> 1) & 3, c & 1
+        v = m * 0.5 if e == 0 else (1.0 + m / 2.0) * 2.0 ** (e - 1)
+        t[c] = -v if s else v
+    return t
+
+
+E2M1 = _e2m1_table()
+_POS4 = E2M1[:8].copy()
+
+
+def e2m1_decode(codes):
+    return E2M1[np.asarray(codes, dtype=np.uint8) & 0xF]
+
+
+def e2m1_encode(v):
+    """nearest E2M1 code: ties to the even code, saturating at +-6, sign of zero kept"""
+    v = np.asarray(v, dtype=np.float64)
+    a = np.minimum(np.abs(v), 6.0)
+    hi = np.minimum(np.searchsorted(_POS4, a, side="left"), 7)
+    lo = np.maximum(hi - 1, 0)
+    dlo, dhi = a - _POS4[lo], _POS4[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return np.where(np.signbit(v), code | 0x8, code).astype(np.uint8)
+
+
+def mx_quantize_fp4(x):
+    """x [..., K] -> (codes uint8 [..., K] one E2M1 code per element, scales uint8 [..., K/32])"""
+    x = np.asarray(x, dtype=np.float64)
+    K = x.shape[-1]
+    if K % BLOCK:
+        raise ValueError("K must be a multiple of 32")
+    if not np.isfinite(x).all():
+        raise ValueError("non-finite input")
+    xb = x.reshape(x.shape[:-1] + (K // BLOCK, BLOCK))
+    amax = np.abs(xb).max(axis=-1)
+    _, e = np.frexp(amax)
+    scode = np.where(amax > 0, np.clip(e.astype(np.int64) - 1 + 127 - 2, 0, 254), 0)
+    codes = e2m1_encode(np.ldexp(xb, (127 - scode)[..., None])).reshape(x.shape)
+    return codes, scode.astype(np.uint8)
+
+
+def pack_fp4(codes):
+    """two codes per byte, the element with the even index in the low nibble"""
+    c = np.asarray(codes, dtype=np.uint8)
+    return (c[..., 0::2] | (c[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_fp4(packed):
+    p = np.asarray(packed, dtype=np.uint8)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), dtype=np.uint8)
+    out[..., 0::2] = p & 0xF
+    out[..., 1::2] = p >> 4
+    return out
+
+
+def mx_dequantize_fp4(codes, scales):
+    codes = np.asarray(codes, dtype=np.uint8)
+    K = codes.shape[-1]
+    v = e2m1_decode(codes).reshape(codes.shape[:-1] + (K // BLOCK, BLOCK))
+    return (v * e8m0_decode(scales)[..., None]).reshape(codes.shape)
+
+
+def mx_linear_w4(xq, xs, wq4, ws, bias=None):
+    """y = deq(x) . deq(W)^T + bias with MXFP8 activations and MXFP4 weights (codes unpacked), float64"""
+    y = mx_dequantize(xq, xs) @ mx_dequantize_fp4(wq4, ws).T
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y

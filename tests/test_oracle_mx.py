@@ -29,7 +29,7 @@ def _gold():
         elif kind == "E8M0":
             c, v = rest.split()
             e8.append((int(c), int(v)))
-        else:
+        elif kind == "BLOCK":
             vals, sc, codes = [p.strip() for p in rest.split("|")]
             blocks.append(([float(t) for t in vals.split()], int(sc), [int(t, 16) for t in codes.split()]))
     return e4, e8, blocks
@@ -240,3 +240,59 @@ def test_bf16_round_matches_torch_and_cut_compress_composes():
     # what the receiver sees differs from the tensor by the bf16 rounding plus one element step
     err = np.abs(mx.mx_dequantize(q, s) - t).max() / np.abs(t).max()
     assert err < 2.0 ** -4 + 2.0 ** -8
+
+
+def _gold4():
+    e2, blocks = [], []
+    for line in open(GOLD):
+        line = line.strip()
+        if line.startswith("E2M1 "):
+            _, c, v = line.split()
+            e2.append((int(c, 16), float(v)))
+        elif line.startswith("BLOCK4 "):
+            vals, sc, codes = [p.strip() for p in line[len("BLOCK4 "):].split("|")]
+            blocks.append(([float(t) for t in vals.split()], int(sc), [int(t, 16) for t in codes.split()]))
+    return e2, blocks
+
+
+def test_fp4_constants_worked_blocks_and_nearest():
+    e2, blocks = _gold4()
+    assert len(e2) == 8 and len(blocks) == 2
+    for c, v in e2:
+        assert mx.e2m1_decode(np.uint8(c)) == v
+    for vals, sc, codes in blocks:
+        x = np.zeros(32); x[:len(vals)] = vals
+        q, s = mx.mx_quantize_fp4(x[None, :])
+        assert int(s[0, 0]) == sc
+        want = np.zeros(32, dtype=np.uint8); want[:len(codes)] = codes
+        np.testing.assert_array_equal(q[0], want)
+    # encode inverts decode on all 16 codes; brute-force nearest with the even code on ties; clamp at 6
+    allc = np.arange(16, dtype=np.uint8)
+    np.testing.assert_array_equal(mx.e2m1_encode(mx.e2m1_decode(allc)), allc)
+    rng = np.random.default_rng(10)
+    v = np.concatenate([rng.uniform(-8, 8, 4000), (mx._POS4[1:] + mx._POS4[:-1]) / 2, -(mx._POS4[1:] + mx._POS4[:-1]) / 2])
+    got = mx.e2m1_encode(v)
+    for x, c in zip(v, got):
+        d = np.abs(mx.E2M1 - x)
+        assert abs(mx.E2M1[c] - x) == d.min()
+        if (d == d.min()).sum() > 1 and x != 0:
+            assert c % 2 == 0
+    # block window: max / scale in [4, 8); packing round trip; exactness on representable data
+    x = (rng.normal(0, 1, (16, 128)) * 10.0 ** rng.uniform(-4, 4, (16, 1)))
+    q, s = mx.mx_quantize_fp4(x)
+    amax = np.abs(x.reshape(16, 4, 32)).max(axis=-1)
+    r = amax / mx.e8m0_decode(s)
+    assert ((r >= 4) & (r < 8)).all()
+    np.testing.assert_array_equal(mx.unpack_fp4(mx.pack_fp4(q)), q)
+    assert mx.pack_fp4(np.array([[0x1, 0xF, 0x7, 0x0]], dtype=np.uint8)).tolist() == [[0xF1, 0x07]]
+    codes = rng.integers(0, 16, (8, 64)).astype(np.uint8); codes[:, ::32] = 0x7
+    sc = rng.integers(110, 140, (8, 2)).astype(np.uint8)
+    q2, s2 = mx.mx_quantize_fp4(mx.mx_dequantize_fp4(codes, sc))
+    np.testing.assert_array_equal(q2 & 7, codes & 7)          # magnitudes (the sign of a zero element may differ)
+    np.testing.assert_array_equal(s2, sc)
+    # the linear with 4-bit weights against explicit loops
+    xq = rng.integers(0, 127, (3, 64)).astype(np.uint8); xs = rng.integers(120, 130, (3, 2)).astype(np.uint8)
+    y = mx.mx_linear_w4(xq, xs, codes, sc)
+    ref = np.array([[sum(mx.E4M3[xq[m, k]] * 2.0 ** (int(xs[m, k // 32]) - 127) * mx.E2M1[codes[n, k]] * 2.0 ** (int(sc[n, k // 32]) - 127)
+                         for k in range(64)) for n in range(8)] for m in range(3)])
+    np.testing.assert_allclose(y, ref, rtol=1e-13, atol=1e-13)
