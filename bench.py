@@ -95,7 +95,7 @@ def mxfp8_leg(cfg, stream):
         torch.cuda.synchronize()
         return (time.perf_counter() - t_) / reps * 1e3
 
-    shapes, flop, ms_mx, ms_bf = [], 0.0, 0.0, 0.0
+    shapes, flop, ms_mx, ms_bf, ms_w4 = [], 0.0, 0.0, 0.0, 0.0
     quant = None
     for name, K, N in (("qkv", d, 3 * d), ("o", d, d), ("fc", d, dff), ("proj", dff, d)):
         x = torch.randn((T, K), device="cuda", generator=g).to(torch.bfloat16)
@@ -112,13 +112,18 @@ def mxfp8_leg(cfg, stream):
             quant = {"ms": tq, "bytes": nbytes, "gb_s": nbytes / (tq * 1e-3) / 1e9}
         t_mx = timed(lambda: B.slora_frozen_linear_mxfp8(T, K, N, xq, xs, wq, ws, None, y, stream))
         t_bf = timed(lambda: B.slora_frozen_linear_bf16(T, K, N, x, W, None, y, stream))
+        wq4 = torch.empty((N, K // 2), dtype=torch.uint8, device="cuda")
+        B.slora_mx_quantize_fp4(N, K, W, K, wq4, ws, stream)
+        t_w4 = timed(lambda: B.slora_frozen_linear_mxfp8_w4(T, K, N, xq, xs, wq4, ws, None, y, stream))
         f = 2.0 * T * K * N
         shapes.append({"name": name, "K": K, "N": N, "mxfp8_us": t_mx * 1e3, "bf16_us": t_bf * 1e3,
-                       "mxfp8_tflops": f / (t_mx * 1e-3) / 1e12})
+                       "mxfp8_tflops": f / (t_mx * 1e-3) / 1e12, "w4_us": t_w4 * 1e3,
+                       "w4_tflops": f / (t_w4 * 1e-3) / 1e12})
+        ms_w4 += t_w4
         flop += f
         ms_mx += t_mx
         ms_bf += t_bf
-        del x, W, xq, xs, wq, ws, y
+        del x, W, xq, xs, wq, ws, y, wq4
     # the whole compressed LoRA layer (conversion of the activations, rank-space branch, fp8 product with the
     # bf16 low-rank tail; backward with the adapter gradients) on the qkv-sized and the FC-sized projection
     layer = []
@@ -147,7 +152,9 @@ def mxfp8_leg(cfg, stream):
     ach = flop / (ms_mx * 1e-3) / 1e12
     return {"lora_layer": layer, "what": "y = deq(x) deq(W)^T, MXFP8 operands (E4M3 + E8M0 per 32), bf16 out, T=%d" % T,
             "shapes": shapes, "tflops": ach, "peak": PEAK_FP8_TFLOPS, "frac": ach / PEAK_FP8_TFLOPS,
-            "speedup_over_bf16_kernel": ms_bf / ms_mx, "quantize_activation": quant}
+            "speedup_over_bf16_kernel": ms_bf / ms_mx, "quantize_activation": quant,
+            "w4_tflops": flop / (ms_w4 * 1e-3) / 1e12,
+            "w4_what": "the same products with MXFP4 (E2M1) weights, MXFP8 activations"}
 
 
 def main():

@@ -215,6 +215,17 @@ int slora_mx_dequantize(int64_t M, int32_t K, const void *codes, const void *sca
 int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void *xq, const void *xs,
                               const void *wq, const void *ws, const void *bias, void *y, void *stream);
 
+/* Frozen weights in 4 bits (MXFP4: FP4 E2M1 elements -- values 0, 0.5, 1, 1.5, 2, 3, 4, 6, no NaN -- under
+ * the same E8M0 scale per 32 elements, 4.25 bits per weight; the paper's pointer for quantisation is a
+ * 4-bit-weight fine-tuning method, Sec. V-B).  slora_mx_quantize_fp4 is slora_mx_quantize with E2M1 elements
+ * (scale code = max(E - 2, 0), clamp at +-6); codes u8 [M, K/2], two per byte, the element with the even
+ * index in the low nibble (4-byte aligned).  slora_frozen_linear_mxfp8_w4 is slora_frozen_linear_mxfp8 with
+ * the weight given in that form (wq4 u8 [n_out, n_in/2], 16-byte aligned); activations stay MXFP8. */
+int slora_mx_quantize_fp4(int64_t M, int32_t K, const void *x, int64_t ldx, void *codes, void *scales,
+                          void *stream);
+int slora_frozen_linear_mxfp8_w4(int32_t T, int32_t n_in, int32_t n_out, const void *xq, const void *xs,
+                                 const void *wq4, const void *ws, const void *bias, void *y, void *stream);
+
 /* One LoRA-adapted linear layer (Sec. II-C) with the frozen product in MXFP8 and the adapter kept in bf16
  * operands / fp32 parameters:
  *   fwd:  y  = deq(Q(x)) . deq(Q(W))^T + bias + s (x A^T) B^T            s = alpha / r

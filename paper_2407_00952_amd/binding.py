@@ -31,7 +31,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_adapters_changed", "slora_adamw", "slora_mx_quantize", "slora_mx_dequantize",
            "slora_frozen_linear_mxfp8", "slora_mx_weight_bytes", "slora_mx_pack_weight",
            "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd",
-           "slora_server_fwd_mx", "slora_server_bwd_mx"]
+           "slora_server_fwd_mx", "slora_server_bwd_mx", "slora_mx_quantize_fp4",
+           "slora_frozen_linear_mxfp8_w4"]
 
 
 class slora_config(ctypes.Structure):
@@ -86,6 +87,8 @@ def lib():
         L.slora_mx_quantize.argtypes = [i64, i32, vp, i64, vp, vp, vp]
         L.slora_mx_dequantize.argtypes = [i64, i32, vp, vp, vp, i64, vp]
         L.slora_frozen_linear_mxfp8.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.slora_mx_quantize_fp4.argtypes = [i64, i32, vp, i64, vp, vp, vp]
+        L.slora_frozen_linear_mxfp8_w4.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.slora_server_fwd_mx.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.slora_server_bwd_mx.argtypes = [vp, vp, vp, vp, vp]
         L.slora_mx_weight_bytes.argtypes = [i32, i32]
@@ -224,6 +227,15 @@ def slora_mx_dequantize(M, K, codes, scales, y, ldy, stream=None):
 def slora_frozen_linear_mxfp8(T, n_in, n_out, xq, xs, wq, ws, bias, y, stream=None):
     _check(lib().slora_frozen_linear_mxfp8(T, n_in, n_out, _p(xq), _p(xs), _p(wq), _p(ws), _p(bias), _p(y),
                                            _stream(stream)))
+
+
+def slora_mx_quantize_fp4(M, K, x, ldx, codes, scales, stream=None):
+    _check(lib().slora_mx_quantize_fp4(M, K, _p(x), ldx, _p(codes), _p(scales), _stream(stream)))
+
+
+def slora_frozen_linear_mxfp8_w4(T, n_in, n_out, xq, xs, wq4, ws, bias, y, stream=None):
+    _check(lib().slora_frozen_linear_mxfp8_w4(T, n_in, n_out, _p(xq), _p(xs), _p(wq4), _p(ws), _p(bias), _p(y),
+                                              _stream(stream)))
 
 
 def slora_mx_weight_bytes(n_in, n_out):

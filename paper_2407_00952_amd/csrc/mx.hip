@@ -65,6 +65,41 @@ __global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict
     }
 }
 
+// The same for FP4 E2M1 elements (frozen weights): emax 2, so the scale code is the biased exponent - 2;
+// two codes per byte, the element with the even index in the low nibble.
+__global__ __launch_bounds__(256) void mx_quantize_fp4_kernel(const bf16 *__restrict__ x, long long ldx, long long M,
+                                                              int K, unsigned char *__restrict__ codes,
+                                                              unsigned char *__restrict__ scales)
+{
+    const int cpr = K >> 3;
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = t < M * cpr;
+    const long long row = live ? t / cpr : 0;
+    const int ch = live ? (int)(t - row * cpr) : 0;
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    if (live) raw = *(const uint4 *)(x + row * ldx + ch * 8);
+    const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+    unsigned mag = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        mag = max(mag, w[i] & 0x7FFFu);
+        mag = max(mag, (w[i] >> 16) & 0x7FFFu);
+    }
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
+    const int scode = max((int)(mag >> 7) - 2, 0);
+    unsigned out = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned h = (i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu);
+        out |= mx_encode_fp4_bf16(h, scode) << (4 * i);
+    }
+    if (live) {
+        *(unsigned *)(codes + row * (long long)(K >> 1) + ch * 4) = out;
+        if ((ch & 3) == 0) scales[row * (long long)(K >> 5) + (ch >> 2)] = (unsigned char)scode;
+    }
+}
+
 __global__ __launch_bounds__(256) void mx_dequantize_kernel(const unsigned char *__restrict__ codes,
                                                             const unsigned char *__restrict__ scales, long long M,
                                                             int K, bf16 *__restrict__ y, long long ldy)
@@ -93,7 +128,7 @@ __global__ __launch_bounds__(256) void mx_dequantize_kernel(const unsigned char 
 // ------------------------------------------------------------------------------------------------
 constexpr int BM = 256, BN = 256, BKB = 128, NTHR = 512;   // BKB: bytes = fp8 elements per slab row
 constexpr int XB = BM * BKB, WB = BN * BKB, SB = BM * 4;   // tile bytes; scale bytes per operand tile
-constexpr int STAGE = XB + WB + 2 * SB;
+constexpr int STAGE = XB + WB + 2 * SB;                    // (fp8 weights; 4-bit weights need half of WB)
 
 struct MxArgs {
     const unsigned char *X, *XS;     // codes [M,K], scales [M,K/32]
@@ -105,6 +140,9 @@ struct MxArgs {
     const bf16 *zs;                  // [M,16]: scaled rank-space activations, zero beyond the rank
     const bf16 *tmat;                // [N,32]: up-projection, zero beyond the rank
 };
+// With W4 the weight operand is MXFP4: W holds two E2M1 codes per byte ([N, K/2]), a tile row is 64 bytes
+// per slab, the lane's 32 elements are 16 consecutive bytes (k = 32g .. 32g+31) and the upper half of the
+// operand register is unused.
 
 __device__ __forceinline__ void glds16(const void *sbase, unsigned voff, unsigned lds)
 {
@@ -121,10 +159,13 @@ __device__ __forceinline__ unsigned lds_addr(const void *p)
 }
 #define MX_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
+template <bool W4>
 __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE];
-    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE];
+    constexpr int WROW = W4 ? 64 : 128;                  // bytes of one tile row of W per slab
+    constexpr int WBt = BN * WROW, STAGEt = XB + WBt + 2 * SB;
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGEt];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGEt];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -157,7 +198,11 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
     const int srow = sx ? min(m0 + wave * 64 + lane, a.M - 1) : min(n0 + (wave - 4) * 64 + lane, a.N - 1);
     const unsigned so = (unsigned)srow * (unsigned)kb4;
     const unsigned char *Sb = sx ? a.XS : a.WS;
-    const int s_lds = XB + WB + (sx ? 0 : SB) + (wave & 3) * 256;
+    const int s_lds = XB + WBt + (sx ? 0 : SB) + (wave & 3) * 256;
+    // 4-bit weights: a copy instruction moves 16 rows of 64 bytes; lane l -> row l>>2, physical chunk l&3
+    // holding logical chunk (l&3) ^ ((row>>1)&3), which keeps the 16-byte operand reads conflict-free
+    const int w4row0 = n0 + wave * 32 + (lane >> 2);
+    const unsigned w4ch16 = (unsigned)(((lane & 3) ^ ((lane >> 3) & 3)) * 16);
     const int wofs = wave * 32 * BKB;
 
     f32x4 acc[8][4];
@@ -176,19 +221,27 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
         asm volatile("" : "+a"(agpr_hint));
     }
 
-    const int a_row = (wm * 128 + r16) * BKB, b_row = (wn * 64 + r16) * BKB;
+    const int a_row = (wm * 128 + r16) * BKB, b_row = (wn * 64 + r16) * WROW;
     const int sw = r16 & 7;
     const int c0 = ((kg ^ sw) << 4), c1 = (((4 + kg) ^ sw) << 4);      // the lane's two 16-byte chunks
-    const int as_off = XB + WB + (wm * 128 + r16) * 4 + kg, bs_off = XB + WB + SB + (wn * 64 + r16) * 4 + kg;
+    const int c4 = ((kg ^ ((r16 >> 1) & 3)) << 4);                      // its one chunk of a 4-bit row
+    const int as_off = XB + WBt + (wm * 128 + r16) * 4 + kg, bs_off = XB + WBt + SB + (wn * 64 + r16) * 4 + kg;
 
 #define MX_ISSUE(st, kt, p)                                                               \
     {                                                                                     \
         int xr_ = xrow0, wr_ = wrow0;                                                     \
         asm volatile("" : "+v"(xr_), "+v"(wr_));                                          \
         const unsigned xo_ = (unsigned)min(xr_ + (p) * 8, a.M - 1) * (unsigned)a.K + lch16; \
-        const unsigned wo_ = (unsigned)min(wr_ + (p) * 8, a.N - 1) * (unsigned)a.K + lch16; \
         glds16(a.X + (size_t)(kt) * BKB, xo_, lds_addr(st) + wofs + (p) * 1024);          \
-        glds16(a.W + (size_t)(kt) * BKB, wo_, lds_addr(st) + XB + wofs + (p) * 1024);     \
+        if (!W4) {                                                                        \
+            const unsigned wo_ = (unsigned)min(wr_ + (p) * 8, a.N - 1) * (unsigned)a.K + lch16; \
+            glds16(a.W + (size_t)(kt) * BKB, wo_, lds_addr(st) + XB + wofs + (p) * 1024); \
+        } else if ((p) < 2) {                                                             \
+            int w4_ = w4row0;                                                             \
+            asm volatile("" : "+v"(w4_));                                                 \
+            const unsigned wo_ = (unsigned)min(w4_ + (p) * 16, a.N - 1) * (unsigned)(a.K >> 1) + w4ch16; \
+            glds16(a.W + (size_t)(kt) * 64, wo_, lds_addr(st) + XB + wave * 2048 + (p) * 1024); \
+        }                                                                                 \
         if ((p) == 0) glds4(Sb + (size_t)(kt) * 4, so, lds_addr(st) + s_lds);             \
     }
 #define MX_FRAG(dst, base, off)                                                           \
@@ -204,7 +257,12 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
         i32x8 bfr[4];                                                                     \
         int bsc[4];                                                                       \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                   \
-            MX_FRAG(bfr[j], S_ + XB, b_row + j * 16 * BKB)                                \
+            if (W4) {                                                                     \
+                bfr[j].lo = *(const i32x4 *)(S_ + XB + b_row + j * 16 * WROW + c4);       \
+                bfr[j].hi = (i32x4){0, 0, 0, 0};                                          \
+            } else {                                                                      \
+                MX_FRAG(bfr[j], S_ + XB, b_row + j * 16 * WROW)                           \
+            }                                                                             \
             bsc[j] = S_[bs_off + j * 64];                                                 \
         }                                                                                 \
         _Pragma("unroll") for (int iq = 0; iq < 4; ++iq) {                                \
@@ -217,7 +275,7 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
             _Pragma("unroll") for (int i = 0; i < 2; ++i)                                 \
                 _Pragma("unroll") for (int j = 0; j < 4; ++j)                             \
                     acc[iq * 2 + i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4( \
-                        af[i], bfr[j], acc[iq * 2 + i][j], 0, 0, 0, asc[i], 0, bsc[j]);   \
+                        af[i], bfr[j], acc[iq * 2 + i][j], 0, W4 ? 4 : 0, 0, asc[i], 0, bsc[j]); \
         }                                                                                 \
     }
 #define MX_PHASE(cur, nxt, kt, doload)                                                    \
@@ -366,10 +424,11 @@ int launch_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned c
     return 0;
 }
 
-int launch_gemm_mx(const MxArgs &a, hipStream_t st)
+int launch_gemm_mx(const MxArgs &a, hipStream_t st, bool w4 = false)
 {
     const int nb = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL(gemm_mx_kernel, dim3(((nb + 7) / 8) * 8), dim3(NTHR), 0, st, a);
+    if (w4) hipLaunchKernelGGL(gemm_mx_kernel<true>, dim3(((nb + 7) / 8) * 8), dim3(NTHR), 0, st, a);
+    else hipLaunchKernelGGL(gemm_mx_kernel<false>, dim3(((nb + 7) / 8) * 8), dim3(NTHR), 0, st, a);
     SL_CHECK_LAUNCH("gemm_mx");
     return 0;
 }
@@ -471,6 +530,38 @@ int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void
     a.M = T; a.N = n_out; a.K = n_in;
     a.zs = nullptr; a.tmat = nullptr;
     return launch_gemm_mx(a, (hipStream_t)stream);
+}
+
+int slora_mx_quantize_fp4(int64_t M, int32_t K, const void *x, int64_t ldx, void *codes, void *scales, void *stream)
+{
+    if (M <= 0 || K <= 0 || (K % 32) || ldx < K || (ldx % 8) || !x || !codes || !scales) return SLORA_EINVAL;
+    if (!aligned(x, 16) || !aligned(codes, 4)) return SLORA_EINVAL;
+    const long long threads = (long long)M * (K / 8);
+    if (threads > (1ll << 31) * 256ll) return SLORA_EINVAL;
+    hipLaunchKernelGGL(mx_quantize_fp4_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (const bf16 *)x, (long long)ldx, (long long)M, (int)K,
+                       (unsigned char *)codes, (unsigned char *)scales);
+    SL_CHECK_LAUNCH("mx_quantize_fp4");
+    return SLORA_OK;
+}
+
+int slora_frozen_linear_mxfp8_w4(int32_t T, int32_t n_in, int32_t n_out, const void *xq, const void *xs,
+                                 const void *wq4, const void *ws, const void *bias, void *y, void *stream)
+{
+    if (T <= 0 || n_in <= 0 || n_out <= 0 || (n_in % 128) || (n_out % 8) || !xq || !xs || !wq4 || !ws || !y)
+        return SLORA_EINVAL;
+    if (!aligned(xq, 16) || !aligned(wq4, 16) || !aligned(xs, 4) || !aligned(ws, 4) || !aligned(y, 16) ||
+        (bias && !aligned(bias, 16)))
+        return SLORA_EINVAL;
+    if ((unsigned long long)T * n_in >= (1ull << 32) || (unsigned long long)n_out * n_in >= (1ull << 32))
+        return SLORA_EINVAL;
+    MxArgs a;
+    a.X = (const unsigned char *)xq; a.XS = (const unsigned char *)xs;
+    a.W = (const unsigned char *)wq4; a.WS = (const unsigned char *)ws;
+    a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
+    a.M = T; a.N = n_out; a.K = n_in;
+    a.zs = nullptr; a.tmat = nullptr;
+    return launch_gemm_mx(a, (hipStream_t)stream, true);
 }
 
 size_t slora_mx_weight_bytes(int32_t n_in, int32_t n_out)

@@ -32,3 +32,20 @@ static __device__ __forceinline__ unsigned mx_encode_bf16(unsigned h, int scode)
     const float v = __uint_as_float((h & 0x7FFFu) << 16);
     return mx_e4m3_from_f32(ldexpf(v, 127 - scode)) | ((h >> 8) & 0x80u);   // exact division by the scale
 }
+
+// FP4 E2M1 (bias 1; values 0, 0.5, 1, 1.5, 2, 3, 4, 6; no NaN) code of one bf16 value under the block's
+// scale code: round to nearest, ties to even, clamp at 6.
+static __device__ __forceinline__ unsigned mx_encode_fp4_bf16(unsigned h, int scode)
+{
+    float a = ldexpf(__uint_as_float((h & 0x7FFFu) << 16), 127 - scode);
+    a = fminf(a, 6.0f);
+    unsigned c;
+    if (a < 1.0f) {
+        c = (unsigned)__builtin_rintf(a * 2.0f);         // multiples of 0.5; 2 is the code of 1.0 itself
+    } else {
+        unsigned b = __float_as_uint(a);
+        b += 0x1FFFFFu + ((b >> 22) & 1u);               // ties to even on the one kept mantissa bit
+        c = (b >> 22) - ((127u - 1u) << 1);              // rebias the exponent
+    }
+    return c | ((h >> 12) & 0x8u);
+}

@@ -172,6 +172,10 @@ def test_mx_argument_checks():
     assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok, None, ok, ok, None, ok, None) == B.SLORA_EINVAL
     assert L.slora_frozen_linear_mxfp8(8, 128, 8, ok + 8, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL
     assert L.slora_frozen_linear_mxfp8(1 << 22, 1024, 8, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL   # 2^32 bytes
+    assert L.slora_mx_quantize_fp4(4, 48, ok, 48, ok, ok, None) == B.SLORA_EINVAL
+    assert L.slora_mx_quantize_fp4(4, 64, ok, 64, ok + 2, ok, None) == B.SLORA_EINVAL
+    assert L.slora_frozen_linear_mxfp8_w4(8, 64, 8, ok, ok, ok, ok, None, ok, None) == B.SLORA_EINVAL
+    assert L.slora_frozen_linear_mxfp8_w4(8, 128, 8, ok, ok, None, ok, None, ok, None) == B.SLORA_EINVAL
     # compressed cut-layer traffic: the same checks as the bf16 calls plus the scale tables
     assert L.slora_server_fwd_mx(None, 1, ok, ok, ok, ok, None) == B.SLORA_EINVAL
     assert L.slora_server_bwd_mx(None, ok, ok, ok, None) == B.SLORA_EINVAL

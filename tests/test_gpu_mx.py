@@ -298,3 +298,72 @@ def test_server_round_with_compressed_cut_traffic():
             assert v <= BF16_TOL + 2.0 ** -4, (k, v)
         else:
             assert v <= BF16_TOL, (k, v)
+
+
+@pytest.mark.parametrize("M,K,ldx", [(64, 128, None), (257, 320, 328), (333, 1024, None)])
+def test_quantize_fp4_bit_exact(M, K, ldx):
+    import torch
+    say("mx fp4 quantize", M, K, ldx)
+    rng = np.random.default_rng(M + 1)
+    x = synth.make_mx_linear_inputs(8, K, M, seed=synth.BASE_SEED + M)["W"]            # [M, K] weight-like
+    x = x * np.exp2(rng.integers(-6, 6, size=(M, 1))).astype(np.float32)
+    x[3] = 0.0
+    # the ties of the worked examples and values that clamp, scaled into one block
+    x[5, :32] = np.concatenate([[7.0, 5.0, 2.5, -3.5, 1.25, 1.75, 0.25, 0.75, 6.0, -6.5], np.zeros(22)]).astype(np.float32) * 0.125
+    x = synth.round_bf16(x.astype(np.float32))
+    ldx = ldx or K
+    buf = np.zeros((M, ldx), dtype=np.float32); buf[:, :K] = x
+    xd = B.to_device_bf16(buf)
+    codes = torch.empty((M, K // 2), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((M, K // 32), dtype=torch.uint8, device="cuda")
+    B.slora_mx_quantize_fp4(M, K, xd, ldx, codes, scales)
+    torch.cuda.synchronize()
+    qo, so_ = mx.mx_quantize_fp4(x)
+    np.testing.assert_array_equal(scales.cpu().numpy(), so_)
+    np.testing.assert_array_equal(codes.cpu().numpy(), mx.pack_fp4(qo))
+
+
+@pytest.mark.parametrize("T,K,N,with_bias", [(256, 128, 256, True), (700, 384, 320, True), (513, 1024, 264, False)])
+def test_linear_w4_on_oracle_codes(T, K, N, with_bias):
+    import torch
+    say("mx linear, 4-bit weights", T, K, N)
+    d = synth.make_mx_linear_inputs(T, K, N, seed=synth.BASE_SEED + T + N + 1)
+    xq, xs = mx.mx_quantize(d["x"])
+    wq, ws = mx.mx_quantize_fp4(d["W"])
+    bias = d["bias"] if with_bias else None
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    B.slora_frozen_linear_mxfp8_w4(T, K, N, t(xq), t(xs), t(mx.pack_fp4(wq)), t(ws),
+                                   None if bias is None else B.to_device_bf16(bias), y)
+    torch.cuda.synchronize()
+    got = B.from_device_bf16(y)
+    ref = mx.mx_linear_w4(xq, xs, wq, ws, bias)
+    e = relerr(got, ref)
+    exact = d["x"].astype(np.float64) @ d["W"].astype(np.float64).T + (0 if bias is None else bias.astype(np.float64))
+    rms = np.sqrt(((got - exact) ** 2).mean() / (exact ** 2).mean())
+    say("   max-norm relative error %.2e; rms against the uncompressed layer %.3f" % (e, rms))
+    assert e <= MX_TOL
+    # one mantissa bit in the weights: element noise 2^-2/sqrt(3) -> about 15 % of the product's rms
+    assert rms < 0.2
+
+
+def test_linear_w4_full_code_range():
+    import torch
+    say("mx linear, 4-bit weights, random codes")
+    rng = np.random.default_rng(19)
+    T, K, N = 256, 256, 256
+    xq = rng.integers(0, 256, (T, K)).astype(np.uint8); xq[(xq & 0x7F) == 0x7F] = 0x01
+    wq = rng.integers(0, 16, (N, K)).astype(np.uint8)
+    wq[0, :16] = np.arange(16, dtype=np.uint8)
+    xs = rng.integers(110, 140, (T, K // 32)).astype(np.uint8)
+    ws = rng.integers(110, 140, (N, K // 32)).astype(np.uint8)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    B.slora_frozen_linear_mxfp8_w4(T, K, N, t(xq), t(xs), t(mx.pack_fp4(wq)), t(ws), None, y)
+    torch.cuda.synchronize()
+    got = B.from_device_bf16(y)
+    ref = mx.mx_linear_w4(xq, xs, wq, ws, None)
+    e = relerr(got, ref)
+    colerr = np.abs(got - ref).max(axis=0) / np.abs(ref).max(axis=0)
+    say("   max-norm relative error %.2e (worst column %.2e)" % (e, colerr.max()))
+    assert e <= MX_TOL and colerr.max() <= 2 * MX_TOL
