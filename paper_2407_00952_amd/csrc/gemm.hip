@@ -15,6 +15,7 @@
 // by asynchronous global->LDS copies (no staging registers), 16-byte XOR-swizzled LDS rows
 // so that both the copies and the MFMA operand reads are bank-conflict free.
 #include "common.h"
+#include "gemm_epilogue.h"
 #include <vector>
 
 namespace {
@@ -22,74 +23,6 @@ namespace {
 constexpr int BM = 256, BN = 256, BK = 64, NTHR = 512;
 constexpr int ROWB = BK * 2;                 // bytes per LDS row (one k-slab of a tile row)
 constexpr int XB = BM * ROWB, WB = BN * ROWB;
-
-// Epilogue operands that come from global memory (the residual stream, or the saved GELU derivative),
-// fetched one 32-row strip ahead of their use so that their latency hides behind the LDS transpose.
-struct AuxRow {
-    float4 r0, r1;       // EPI_RESID: 8 fp32 residual values
-    bf16x8 f;            // EPI_DGELU: 8 bf16 values of GELU'(f) saved by the forward
-};
-
-template <int EPI>
-__device__ __forceinline__ void load_aux(const GemmArgs &a, int row, int col, bool ok, AuxRow &x)
-{
-    if (EPI == EPI_RESID) {
-        x.r0 = make_float4(0.f, 0.f, 0.f, 0.f);
-        x.r1 = x.r0;
-        if (ok) {
-            const float *p = (const float *)a.aux + (size_t)row * a.ldo + col;
-            x.r0 = *(const float4 *)p;
-            x.r1 = *(const float4 *)(p + 4);
-        }
-    } else if (EPI == EPI_DGELU) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x.f[i] = f2bf(0.f);
-        if (ok) x.f = *(const bf16x8 *)((const bf16 *)a.aux + (size_t)row * a.ldo + col);
-    }
-}
-
-// Epilogue on 8 consecutive columns of one output row (v already holds acc + bias).
-template <int EPI>
-__device__ __forceinline__ void store_row8(const GemmArgs &a, int row, int col, float (&v)[8], const AuxRow &x)
-{
-    const size_t o = (size_t)row * a.ldo + col;
-    if (EPI == EPI_STORE) {
-        bf16x8 w;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i]);
-        *(bf16x8 *)((bf16 *)a.out0 + o) = w;
-    } else if (EPI == EPI_RESID) {
-        v[0] += x.r0.x; v[1] += x.r0.y; v[2] += x.r0.z; v[3] += x.r0.w;
-        v[4] += x.r1.x; v[5] += x.r1.y; v[6] += x.r1.z; v[7] += x.r1.w;
-        if (a.out0) {
-            *(float4 *)((float *)a.out0 + o) = make_float4(v[0], v[1], v[2], v[3]);
-            *(float4 *)((float *)a.out0 + o + 4) = make_float4(v[4], v[5], v[6], v[7]);
-        }
-        if (a.out1) {
-            bf16x8 w;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i]);
-            *(bf16x8 *)((bf16 *)a.out1 + o) = w;
-        }
-    } else if (EPI == EPI_GELU) {
-        bf16x8 wf, wg;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            // out0 keeps GELU'(f) (all the backward needs of f), out1 = GELU(f)
-            float gv, gd;
-            gelu_fwd_bwd(v[i], gv, gd);
-            wf[i] = f2bf(gd);
-            wg[i] = f2bf(gv);
-        }
-        *(bf16x8 *)((bf16 *)a.out0 + o) = wf;
-        *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
-    } else {   // EPI_DGELU
-        bf16x8 w;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * bf2f(x.f[i]));   // aux holds GELU'(f)
-        *(bf16x8 *)((bf16 *)a.out0 + o) = w;
-    }
-}
 
 // asynchronous global -> LDS copy of 16 bytes per lane: the 64 lanes fill 1 KB starting at `lp`
 #define SL_GLDS(gp, lp)                                                                            \

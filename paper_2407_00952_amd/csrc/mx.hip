@@ -19,6 +19,7 @@
 // rows 4g + e.
 #include "../../include/slora.h"
 #include "common.h"
+#include "gemm_epilogue.h"
 #include "mx_codec.h"
 
 namespace {
@@ -132,13 +133,16 @@ constexpr int STAGE = XB + WB + 2 * SB;                    // (fp8 weights; 4-bi
 
 struct MxArgs {
     const unsigned char *X, *XS;     // codes [M,K], scales [M,K/32]
-    const unsigned char *W, *WS;     // codes [N,K], scales [N,K/32]
+    const unsigned char *W, *WS;     // codes [N,K], scales [N,K/32]   (N = nseg * seg_n)
     const bf16 *bias;                // [N] or null
-    bf16 *out;                       // [M,N]
     int M, N, K;
-    // low-rank branch kept in bf16 (null zs = none): out += zs . tmat^T
-    const bf16 *zs;                  // [M,16]: scaled rank-space activations, zero beyond the rank
-    const bf16 *tmat;                // [N,32]: up-projection, zero beyond the rank
+    int nseg, seg_n;
+    // low-rank branch kept in bf16, per segment (null zs = segment not adapted): out += zs . tmat^T
+    const bf16 *zs[3];               // [M,K2]: scaled rank-space activations, zero beyond the rank(s)
+    const bf16 *tmat[3];             // [seg_n,ldt]: up-projection(s), ldt = K2 rounded up to 32, zero padded
+    int K2, ldt;
+    // epilogue (meaning as in GemmArgs)
+    void *out0; void *out1; const void *aux; int ldo;
 };
 // With W4 the weight operand is MXFP4: W holds two E2M1 codes per byte ([N, K/2]), a tile row is 64 bytes
 // per slab, the lane's 32 elements are 16 consecutive bytes (k = 32g .. 32g+31) and the upper half of the
@@ -159,7 +163,7 @@ __device__ __forceinline__ unsigned lds_addr(const void *p)
 }
 #define MX_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
-template <bool W4>
+template <bool W4, int EPI>
 __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
 {
     constexpr int WROW = W4 ? 64 : 128;                  // bytes of one tile row of W per slab
@@ -173,7 +177,8 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
     const int r16 = lane & 15, kg = lane >> 4;
 
     // consecutive logical tiles go to the same XCD; inside an XCD's range panels of 4 row tiles
-    const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
+    const int tiles_n_seg = (a.seg_n + BN - 1) / BN;
+    const int tiles_n = tiles_n_seg * a.nseg, tiles_m = (a.M + BM - 1) / BM;
     const int nb = tiles_m * tiles_n;
     const int per_xcd = (nb + 7) >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -182,7 +187,8 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
     const int pidx = logical / (PANEL * tiles_n), prem = logical - pidx * (PANEL * tiles_n);
     const int prow = min(PANEL, tiles_m - pidx * PANEL);
     const int tn = prem / prow, tm = pidx * PANEL + prem - tn * prow;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int seg = tn / tiles_n_seg, tns = tn - seg * tiles_n_seg;
+    const int m0 = tm * BM, n0 = seg * a.seg_n + tns * BN, n_end = (seg + 1) * a.seg_n;
 
     // ---- copies: per stage every wave moves 32 rows of each tile (8 rows = 1 KB per instruction, lane l
     //      -> row l>>3, physical 16-byte chunk l&7 holding logical chunk (l&7)^(l>>3)) and 64 rows' scale
@@ -195,7 +201,7 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
     const unsigned lch16 = lch * 16;
     const int kb4 = a.K >> 5;                            // scale bytes per row
     const bool sx = wave < 4;
-    const int srow = sx ? min(m0 + wave * 64 + lane, a.M - 1) : min(n0 + (wave - 4) * 64 + lane, a.N - 1);
+    const int srow = sx ? min(m0 + wave * 64 + lane, a.M - 1) : min(n0 + (wave - 4) * 64 + lane, n_end - 1);
     const unsigned so = (unsigned)srow * (unsigned)kb4;
     const unsigned char *Sb = sx ? a.XS : a.WS;
     const int s_lds = XB + WBt + (sx ? 0 : SB) + (wave & 3) * 256;
@@ -234,12 +240,12 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
         const unsigned xo_ = (unsigned)min(xr_ + (p) * 8, a.M - 1) * (unsigned)a.K + lch16; \
         glds16(a.X + (size_t)(kt) * BKB, xo_, lds_addr(st) + wofs + (p) * 1024);          \
         if (!W4) {                                                                        \
-            const unsigned wo_ = (unsigned)min(wr_ + (p) * 8, a.N - 1) * (unsigned)a.K + lch16; \
+            const unsigned wo_ = (unsigned)min(wr_ + (p) * 8, n_end - 1) * (unsigned)a.K + lch16; \
             glds16(a.W + (size_t)(kt) * BKB, wo_, lds_addr(st) + XB + wofs + (p) * 1024); \
         } else if ((p) < 2) {                                                             \
             int w4_ = w4row0;                                                             \
             asm volatile("" : "+v"(w4_));                                                 \
-            const unsigned wo_ = (unsigned)min(w4_ + (p) * 16, a.N - 1) * (unsigned)(a.K >> 1) + w4ch16; \
+            const unsigned wo_ = (unsigned)min(w4_ + (p) * 16, n_end - 1) * (unsigned)(a.K >> 1) + w4ch16; \
             glds16(a.W + (size_t)(kt) * 64, wo_, lds_addr(st) + XB + wave * 2048 + (p) * 1024); \
         }                                                                                 \
         if ((p) == 0) glds4(Sb + (size_t)(kt) * 4, so, lds_addr(st) + s_lds);             \
@@ -307,31 +313,36 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
 #undef MX_STEP
 #undef MX_PHASE
 
-    // ---- low-rank tail (SplitLoRA Sec. II-C: W + BA with the adapter kept in bf16): one bf16 MFMA k-step
-    //      of 32 per tile on operands read straight from global memory (1 MB and 256 KB: cache hits);
-    //      k = 16..31 of both operands is zero padding
-    if (a.zs != nullptr) {
-        bf16x8 tb[4];
+    // ---- low-rank tail (SplitLoRA Sec. II-C: W + BA with the adapter kept in bf16): ldt / 32 bf16 MFMA
+    //      k-steps per tile on operands read straight from global memory (a few MB: cache hits); columns
+    //      of the rank-space activations beyond K2 and of the up-projection beyond the ranks are zero
+    if (a.zs[seg] != nullptr) {
+        const bf16 *zs_ = a.zs[seg], *tm_ = a.tmat[seg];
+        for (int ks = 0; ks < (a.ldt >> 5); ++ks) {
+            bf16x8 tb[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = min(n0 + wn * 64 + j * 16 + r16, a.N - 1);
-            tb[j] = *(const bf16x8 *)(a.tmat + (size_t)n * 32 + kg * 8);
-        }
+            for (int j = 0; j < 4; ++j) {
+                const int n = min(n0 + wn * 64 + j * 16 + r16, n_end - 1) - seg * a.seg_n;
+                tb[j] = *(const bf16x8 *)(tm_ + (size_t)n * a.ldt + ks * 32 + kg * 8);
+            }
+            const bool zok = ks * 32 + kg * 8 < a.K2;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = min(m0 + wm * 128 + i * 16 + r16, a.M - 1);
-            bf16x8 za;
+            for (int i = 0; i < 8; ++i) {
+                const int row = min(m0 + wm * 128 + i * 16 + r16, a.M - 1);
+                bf16x8 za;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) za[q] = f2bf(0.f);
-            if (kg < 2) za = *(const bf16x8 *)(a.zs + (size_t)row * 16 + kg * 8);
+                for (int q = 0; q < 8; ++q) za[q] = f2bf(0.f);
+                if (zok) za = *(const bf16x8 *)(zs_ + (size_t)row * a.K2 + ks * 32 + kg * 8);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(za, tb[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(za, tb[j], acc[i][j], 0, 0, 0);
+            }
         }
     }
 
     // ---- epilogue: each wave transposes its tiles through a private LDS strip (32 rows x 64 columns
-    //      fp32) so that global memory sees 16-byte accesses; only the owning wave touches its strip
+    //      fp32) so that global memory sees 16-byte accesses; only the owning wave touches its strip.
+    //      The operands that come from global memory are fetched one strip ahead.
     constexpr int EP = 68;
     float *stg = (float *)((wave < 4 ? st0 : st1) + (wave & 3) * (32 * EP * 4));
     const int er = lane >> 3, ec = (lane & 7) * 8;
@@ -341,12 +352,26 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
         bf16x8 b8;
 #pragma unroll
         for (int i = 0; i < 8; ++i) b8[i] = f2bf(0.f);
-        if (a.bias && gcol < a.N) b8 = *(const bf16x8 *)(a.bias + gcol);
+        if (a.bias && gcol < n_end) b8 = *(const bf16x8 *)(a.bias + gcol);
 #pragma unroll
         for (int i = 0; i < 8; ++i) bias8[i] = bf2f(b8[i]);
     }
+    AuxRow aux[2][4];
+    const int row_base = m0 + wm * 128 + er;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int row = row_base + it * 8;
+        load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[0][it]);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+        if (i + 1 < 4) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = row_base + (i + 1) * 32 + it * 8;
+                load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[(i + 1) & 1][it]);
+            }
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -359,56 +384,63 @@ __global__ __launch_bounds__(NTHR) void gemm_mx_kernel(MxArgs a)
             const int rl = it * 8 + er;
             const float4 p0 = *(const float4 *)(stg + rl * EP + ec);
             const float4 p1 = *(const float4 *)(stg + rl * EP + ec + 4);
-            const float v[8] = {p0.x + bias8[0], p0.y + bias8[1], p0.z + bias8[2], p0.w + bias8[3],
-                                p1.x + bias8[4], p1.y + bias8[5], p1.z + bias8[6], p1.w + bias8[7]};
+            float v[8] = {p0.x + bias8[0], p0.y + bias8[1], p0.z + bias8[2], p0.w + bias8[3],
+                          p1.x + bias8[4], p1.y + bias8[5], p1.z + bias8[6], p1.w + bias8[7]};
             const int row = m0 + wm * 128 + i * 32 + rl;
-            if (row < a.M && gcol < a.N) {
-                bf16x8 w;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) w[q] = f2bf(v[q]);
-                *(bf16x8 *)(a.out + (size_t)row * a.N + gcol) = w;
-            }
+            if (row < a.M && gcol < n_end) store_row8<EPI>(a, row, gcol, v, aux[i & 1][it]);
         }
     }
 }
 
-// Rank-space activations of the bf16 adapter branch: out[M,16] = scale * X[M,K] . Z[16,K]^T (rows of Z
-// beyond the rank are zero), rounded to bf16.  One wave per 16 rows, operands straight from global memory
-// (the kernel reads X once: HBM-bound), four independent accumulators for the four k-steps in flight.
+// Rank-space activations of the bf16 adapter branch: out[M, 16 NT] = scale * X[M,K] . Z[16 NT, K]^T (rows of
+// Z beyond the ranks are zero), rounded to bf16.  One wave per 16 rows, operands straight from global memory
+// (the kernel reads X once: HBM-bound), two k-steps in flight per column tile.
+template <int NT>
 __global__ __launch_bounds__(256) void rank_project_kernel(const bf16 *__restrict__ X, long long ldx, int M, int K,
-                                                           const bf16 *__restrict__ Z, float scale,
+                                                           const bf16 *__restrict__ Z, long long ldz, float scale,
                                                            bf16 *__restrict__ out)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15, kg = lane >> 4;
     const int row0 = (blockIdx.x * 4 + wave) * 16;
     if (row0 >= M) return;
     const bf16 *xp = X + (size_t)min(row0 + r16, M - 1) * ldx + kg * 8;
-    const bf16 *zp = Z + (size_t)r16 * K + kg * 8;
-    f32x4 acc[4];
+    const bf16 *zp = Z + (size_t)r16 * ldz + kg * 8;
+    f32x4 acc[NT][2];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[u][e] = 0.f;
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[t][u][e] = 0.f;
     int k0 = 0;
-    for (; k0 + 128 <= K; k0 += 128) {
-        bf16x8 xa[4], zb[4];
+    for (; k0 + 64 <= K; k0 += 64) {
+        bf16x8 xa[2], zb[NT][2];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 2; ++u) {
             xa[u] = *(const bf16x8 *)(xp + k0 + u * 32);
-            zb[u] = *(const bf16x8 *)(zp + k0 + u * 32);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) zb[t][u] = *(const bf16x8 *)(zp + (size_t)t * 16 * ldz + k0 + u * 32);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[u], zb[u], acc[u], 0, 0, 0);
-    }
-    for (; k0 < K; k0 += 32)
-        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8 *)(xp + k0), *(const bf16x8 *)(zp + k0), acc[0],
-                                                         0, 0, 0);
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int row = row0 + 4 * kg + e;
-        const float v = ((acc[0][e] + acc[1][e]) + (acc[2][e] + acc[3][e])) * scale;
-        if (row < M) out[(size_t)row * 16 + r16] = f2bf(v);
+            for (int u = 0; u < 2; ++u)
+                acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[u], zb[t][u], acc[t][u], 0, 0, 0);
     }
+    for (; k0 < K; k0 += 32) {
+        const bf16x8 xa = *(const bf16x8 *)(xp + k0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, *(const bf16x8 *)(zp + (size_t)t * 16 * ldz + k0),
+                                                                acc[t][0], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int row = row0 + 4 * kg + e;
+            if (row < M) out[(size_t)row * (16 * NT) + t * 16 + r16] = f2bf((acc[t][0][e] + acc[t][1][e]) * scale);
+        }
 }
 
 bool aligned(const void *p, uintptr_t n) { return (((uintptr_t)p) & (n - 1)) == 0; }
@@ -424,19 +456,52 @@ int launch_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned c
     return 0;
 }
 
-int launch_gemm_mx(const MxArgs &a, hipStream_t st, bool w4 = false)
+int launch_gemm_mx(const MxArgs &a, hipStream_t st, bool w4 = false, int epi = EPI_STORE)
 {
-    const int nb = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    if (w4) hipLaunchKernelGGL(gemm_mx_kernel<true>, dim3(((nb + 7) / 8) * 8), dim3(NTHR), 0, st, a);
-    else hipLaunchKernelGGL(gemm_mx_kernel<false>, dim3(((nb + 7) / 8) * 8), dim3(NTHR), 0, st, a);
+    const int nb = ((a.M + BM - 1) / BM) * (((a.seg_n + BN - 1) / BN) * a.nseg);
+    const dim3 grid(((nb + 7) / 8) * 8), block(NTHR);
+    if (w4) {
+        if (epi != EPI_STORE) return -1;
+        hipLaunchKernelGGL((gemm_mx_kernel<true, EPI_STORE>), grid, block, 0, st, a);
+    } else {
+        switch (epi) {
+        case EPI_STORE: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_STORE>), grid, block, 0, st, a); break;
+        case EPI_RESID: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_RESID>), grid, block, 0, st, a); break;
+        case EPI_GELU: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_GELU>), grid, block, 0, st, a); break;
+        case EPI_DGELU: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_DGELU>), grid, block, 0, st, a); break;
+        default: return -1;
+        }
+    }
     SL_CHECK_LAUNCH("gemm_mx");
     return 0;
 }
 
-int launch_rank_project(const bf16 *X, long long ldx, int M, int K, const bf16 *Z, float scale, bf16 *out,
-                        hipStream_t st)
+// a plain product: one segment, no adapter branch, bf16 output [M,N]
+MxArgs mx_plain(const void *xq, const void *xs, const void *wq, const void *ws, const void *bias, void *y, int M,
+                int N, int K)
 {
-    hipLaunchKernelGGL(rank_project_kernel, dim3((M + 63) / 64), dim3(256), 0, st, X, ldx, M, K, Z, scale, out);
+    MxArgs a;
+    a.X = (const unsigned char *)xq; a.XS = (const unsigned char *)xs;
+    a.W = (const unsigned char *)wq; a.WS = (const unsigned char *)ws;
+    a.bias = (const bf16 *)bias;
+    a.M = M; a.N = N; a.K = K;
+    a.nseg = 1; a.seg_n = N;
+    for (int i = 0; i < 3; ++i) { a.zs[i] = nullptr; a.tmat[i] = nullptr; }
+    a.K2 = 16; a.ldt = 32;
+    a.out0 = y; a.out1 = nullptr; a.aux = nullptr; a.ldo = N;
+    return a;
+}
+
+int launch_rank_project(const bf16 *X, long long ldx, int M, int K, const bf16 *Z, long long ldz, int nz, float scale,
+                        bf16 *out, hipStream_t st)
+{
+    const dim3 grid((M + 63) / 64), block(256);
+    switch (nz) {
+    case 16: hipLaunchKernelGGL((rank_project_kernel<1>), grid, block, 0, st, X, ldx, M, K, Z, ldz, scale, out); break;
+    case 32: hipLaunchKernelGGL((rank_project_kernel<2>), grid, block, 0, st, X, ldx, M, K, Z, ldz, scale, out); break;
+    case 48: hipLaunchKernelGGL((rank_project_kernel<3>), grid, block, 0, st, X, ldx, M, K, Z, ldz, scale, out); break;
+    default: return -1;
+    }
     SL_CHECK_LAUNCH("rank_project");
     return 0;
 }
@@ -523,13 +588,7 @@ int slora_frozen_linear_mxfp8(int32_t T, int32_t n_in, int32_t n_out, const void
     // the copies address both operands with 32-bit byte offsets from their bases
     if ((unsigned long long)T * n_in >= (1ull << 32) || (unsigned long long)n_out * n_in >= (1ull << 32))
         return SLORA_EINVAL;
-    MxArgs a;
-    a.X = (const unsigned char *)xq; a.XS = (const unsigned char *)xs;
-    a.W = (const unsigned char *)wq; a.WS = (const unsigned char *)ws;
-    a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
-    a.M = T; a.N = n_out; a.K = n_in;
-    a.zs = nullptr; a.tmat = nullptr;
-    return launch_gemm_mx(a, (hipStream_t)stream);
+    return launch_gemm_mx(mx_plain(xq, xs, wq, ws, bias, y, T, n_out, n_in), (hipStream_t)stream);
 }
 
 int slora_mx_quantize_fp4(int64_t M, int32_t K, const void *x, int64_t ldx, void *codes, void *scales, void *stream)
@@ -555,13 +614,7 @@ int slora_frozen_linear_mxfp8_w4(int32_t T, int32_t n_in, int32_t n_out, const v
         return SLORA_EINVAL;
     if ((unsigned long long)T * n_in >= (1ull << 32) || (unsigned long long)n_out * n_in >= (1ull << 32))
         return SLORA_EINVAL;
-    MxArgs a;
-    a.X = (const unsigned char *)xq; a.XS = (const unsigned char *)xs;
-    a.W = (const unsigned char *)wq4; a.WS = (const unsigned char *)ws;
-    a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
-    a.M = T; a.N = n_out; a.K = n_in;
-    a.zs = nullptr; a.tmat = nullptr;
-    return launch_gemm_mx(a, (hipStream_t)stream, true);
+    return launch_gemm_mx(mx_plain(xq, xs, wq4, ws, bias, y, T, n_out, n_in), (hipStream_t)stream, true);
 }
 
 size_t slora_mx_weight_bytes(int32_t n_in, int32_t n_out)
@@ -609,15 +662,12 @@ int slora_mx_lora_linear_fwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, 
     int rc;
     if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 16, n_in, 0, st))) return rc;
     if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B32), n_out, 32, 0, st))) return rc;
-    if ((rc = launch_rank_project((const bf16 *)x, n_in, T, n_in, (const bf16 *)(base + w.A16), s,
+    if ((rc = launch_rank_project((const bf16 *)x, n_in, T, n_in, (const bf16 *)(base + w.A16), n_in, 16, s,
                                   (bf16 *)(base + w.zs), st)))
         return rc;
     if ((rc = launch_quantize((const bf16 *)x, n_in, T, n_in, base + w.q, base + w.qs, st))) return rc;
-    MxArgs a;
-    a.X = base + w.q; a.XS = base + w.qs; a.W = pw + p.wq; a.WS = pw + p.ws;
-    a.bias = (const bf16 *)bias; a.out = (bf16 *)y;
-    a.M = T; a.N = n_out; a.K = n_in;
-    a.zs = (const bf16 *)(base + w.zs); a.tmat = (const bf16 *)(base + w.B32);
+    MxArgs a = mx_plain(base + w.q, base + w.qs, pw + p.wq, pw + p.ws, bias, y, T, n_out, n_in);
+    a.zs[0] = (const bf16 *)(base + w.zs); a.tmat[0] = (const bf16 *)(base + w.B32);
     return launch_gemm_mx(a, st);
 }
 
@@ -639,20 +689,17 @@ int slora_mx_lora_linear_bwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, 
     int rc;
     // zs = s x A^T (for dB) and ps = s dy B (for dA and for the low-rank part of dx)
     if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A16), 16, n_in, 0, st))) return rc;
-    if ((rc = launch_rank_project((const bf16 *)x, n_in, T, n_in, (const bf16 *)(base + w.A16), s,
+    if ((rc = launch_rank_project((const bf16 *)x, n_in, T, n_in, (const bf16 *)(base + w.A16), n_in, 16, s,
                                   (bf16 *)(base + w.zs), st)))
         return rc;
     if ((rc = launch_cast_pad(B, n_out, r, (bf16 *)(base + w.B16T), 16, n_out, 1, st))) return rc;
     if ((rc = launch_cast_pad(A, r, n_in, (bf16 *)(base + w.A32T), n_in, 32, 1, st))) return rc;
-    if ((rc = launch_rank_project((const bf16 *)dy, n_out, T, n_out, (const bf16 *)(base + w.B16T), s,
+    if ((rc = launch_rank_project((const bf16 *)dy, n_out, T, n_out, (const bf16 *)(base + w.B16T), n_out, 16, s,
                                   (bf16 *)(base + w.ps), st)))
         return rc;
     if ((rc = launch_quantize((const bf16 *)dy, n_out, T, n_out, base + w.q, base + w.qs, st))) return rc;
-    MxArgs a;
-    a.X = base + w.q; a.XS = base + w.qs; a.W = pw + p.tq; a.WS = pw + p.ts;
-    a.bias = nullptr; a.out = (bf16 *)dx;
-    a.M = T; a.N = n_in; a.K = n_out;
-    a.zs = (const bf16 *)(base + w.ps); a.tmat = (const bf16 *)(base + w.A32T);
+    MxArgs a = mx_plain(base + w.q, base + w.qs, pw + p.tq, pw + p.ts, nullptr, dx, T, n_in, n_out);
+    a.zs[0] = (const bf16 *)(base + w.ps); a.tmat[0] = (const bf16 *)(base + w.A32T);
     if ((rc = launch_gemm_mx(a, st))) return rc;
     float *part = (float *)(base + w.part);
     if ((rc = launch_lora_grad((const bf16 *)x, n_in, n_in, (const bf16 *)(base + w.ps), 16, r, T, part, dA, 1, st)))
