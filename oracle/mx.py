@@ -227,3 +227,42 @@ def mx_linear_w4(xq, xs, wq4, ws, bias=None):
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float64)[None, :]
     return y
+
+
+# ---- the server stack with every frozen product in MXFP8 (a context of type SLORA_DTYPE_MXFP8) --------------
+# Each linear layer of a block (q, k, v, o, fc, proj; Sec. III-A) is the compressed LoRA layer above, applied
+# to the operand as the bf16 tensor it is stored as: Q(bf16(x)) forward, Q(bf16(dy)) and Q(W^T) backward.
+# LayerNorm, attention, GELU and the residual stream are the uncompressed model's.
+
+def _mx_lin_fwd(x, lin, adapters, name, s):
+    W, b = lin[name]
+    A, B = adapters.get(name, (None, None))
+    x = np.asarray(x, dtype=np.float64)
+    y = mx_linear(*mx_quantize(bf16_round(x)), *mx_quantize(W), b)
+    if A is not None:
+        y = y + s * ((x @ np.asarray(A, dtype=np.float64).T) @ np.asarray(B, dtype=np.float64).T)
+    return y
+
+
+def _mx_lin_bwd(x, dy, lin, adapters, name, s, grads):
+    W, _ = lin[name]
+    A, B = adapters.get(name, (None, None))
+    x, dy = np.asarray(x, dtype=np.float64), np.asarray(dy, dtype=np.float64)
+    dx = mx_linear(*mx_quantize(bf16_round(dy)), *mx_quantize(np.ascontiguousarray(np.asarray(W).T)), None)
+    if A is not None:
+        A, B = np.asarray(A, dtype=np.float64), np.asarray(B, dtype=np.float64)
+        p = dy @ B
+        dx = dx + s * (p @ A)
+        grads[name] = (s * (p.T @ x), s * (dy.T @ (x @ A.T)))
+    return dx
+
+
+def make_mx_server_oracle(blocks, adapters, n_head, lora_alpha, lora_r, eps=1e-5):
+    """the stack oracle of slora_oracle.py with the two functions above in place of the exact linear layer"""
+    from .slora_oracle import ServerOracle
+
+    class MxServerOracle(ServerOracle):
+        lin_fwd = staticmethod(_mx_lin_fwd)
+        lin_bwd = staticmethod(_mx_lin_bwd)
+
+    return MxServerOracle(blocks, adapters, n_head, lora_alpha, lora_r, eps)

@@ -183,8 +183,9 @@ def _lin_bwd(x, dy, lin, adapters, name, s, grads):
     return dx
 
 
-def block_fwd(h, blk, adapters, n_head, s, eps):
-    """h [S,d] -> (h_out [S,d], saved)."""
+def block_fwd(h, blk, adapters, n_head, s, eps, _lin_fwd=_lin_fwd):
+    """h [S,d] -> (h_out [S,d], saved).  (`_lin_fwd`: how a linear layer is evaluated; oracle/mx.py passes the
+    variant with the frozen product in MXFP8.)"""
     h = _f64(h)
     d = h.shape[1]
     lin = _split_qkv(blk, d)
@@ -202,7 +203,7 @@ def block_fwd(h, blk, adapters, n_head, s, eps):
     return h2, saved
 
 
-def block_bwd(dh2, blk, adapters, n_head, s, saved):
+def block_bwd(dh2, blk, adapters, n_head, s, saved, _lin_bwd=_lin_bwd):
     """dh2 [S,d] -> (dh [S,d], {proj: (dA, dB)})."""
     dh2 = _f64(dh2)
     d = dh2.shape[1]
@@ -232,6 +233,10 @@ class ServerOracle:
     adapters : list (length L) of dicts {proj: (A [r,in], B [out,r])}, proj in PROJ_NAMES
     """
 
+    # how a linear layer is evaluated forward and backward (a subclass may replace the pair)
+    lin_fwd = staticmethod(_lin_fwd)
+    lin_bwd = staticmethod(_lin_bwd)
+
     def __init__(self, blocks, adapters, n_head, lora_alpha, lora_r, eps=1e-5):
         self.blocks = blocks
         self.adapters = [{p: (_f64(A).copy(), _f64(B).copy()) for p, (A, B) in ad.items()}
@@ -248,7 +253,7 @@ class ServerOracle:
         h = _f64(h0)
         saved = []
         for blk, ad in zip(self.blocks, self.adapters):
-            h, sv = block_fwd(h, blk, ad, self.n_head, self.s, self.eps)
+            h, sv = block_fwd(h, blk, ad, self.n_head, self.s, self.eps, self.lin_fwd)
             saved.append(sv)
         return h, saved
 
@@ -257,7 +262,7 @@ class ServerOracle:
         grads = [None] * len(self.blocks)
         for l in range(len(self.blocks) - 1, -1, -1):
             dh, grads[l] = block_bwd(dh, self.blocks[l], self.adapters[l], self.n_head,
-                                     self.s, saved[l])
+                                     self.s, saved[l], self.lin_bwd)
         return dh, grads
 
     def fwd_bwd_sequence(self, h0, dy):

@@ -296,3 +296,40 @@ def test_fp4_constants_worked_blocks_and_nearest():
     ref = np.array([[sum(mx.E4M3[xq[m, k]] * 2.0 ** (int(xs[m, k // 32]) - 127) * mx.E2M1[codes[n, k]] * 2.0 ** (int(sc[n, k // 32]) - 127)
                          for k in range(64)) for n in range(8)] for m in range(3)])
     np.testing.assert_allclose(y, ref, rtol=1e-13, atol=1e-13)
+
+
+def test_mx_stack_oracle_reduces_to_the_exact_stack_and_stays_close():
+    """(a) with operands MXFP8 stores exactly the compressed block IS the exact block; (b) on ordinary data
+    the compressed stack stays within the noise budget of the exact one and its adapter gradients are the
+    exact formulas applied to its own activations (checked by finite differences of the exact-adapter part)."""
+    from oracle import slora_oracle as so
+    from paper_2407_00952_amd import synth
+    cfg = synth.tiny_config(d_model=128, n_head=2, d_ff=256, n_blocks=2, lora_r=4, lora_proj=("q", "v", "fc"),
+                            n_clients=2, batch=1, seq_len=64)
+    inp = synth.make_stack_inputs(cfg)
+    exact = so.ServerOracle(inp["blocks"], inp["adapters"], cfg.n_head, cfg.lora_alpha, cfg.lora_r, cfg.ln_eps)
+    comp = mx.make_mx_server_oracle(inp["blocks"], inp["adapters"], cfg.n_head, cfg.lora_alpha, cfg.lora_r, cfg.ln_eps)
+    Ye, Yc = exact.fwd(inp["clients"]), comp.fwd(inp["clients"])
+    dXe, dXc = exact.bwd(inp["dY"]), comp.bwd(inp["dY"])
+    rel = lambda a, b: np.abs(a - b).max() / np.abs(b).max()
+    assert 1e-4 < rel(Yc, Ye) < 0.1
+    for a, b in zip(dXc, dXe):
+        assert 1e-4 < rel(a, b) < 0.25
+    for gl_c, gl_e in zip(comp.grads, exact.grads):
+        for p in gl_e:
+            assert rel(gl_c[p][0], gl_e[p][0]) < 0.3 and rel(gl_c[p][1], gl_e[p][1]) < 0.3
+    # the linear-layer pair itself against the exact pair on representable operands
+    rng = np.random.default_rng(12)
+    x, dy = _representable(rng, (16, 64)), _representable(rng, (16, 96))
+    Wc = mx.e4m3_decode(rng.integers(1, 127, (96, 64)).astype(np.uint8))
+    for i in range(0, 96, 32):
+        for j in range(0, 64, 32):
+            t = Wc[i:i + 32, j:j + 32]; np.fill_diagonal(t, 448.0); t *= 2.0 ** -10
+    A, B = rng.normal(0, 0.1, (3, 64)), rng.normal(0, 0.1, (96, 3))
+    lin, ad = {"fc": (Wc, rng.normal(0, 1, 96))}, {"fc": (A, B)}
+    np.testing.assert_allclose(mx._mx_lin_fwd(x, lin, ad, "fc", 2.5), so._lin_fwd(x, lin, ad, "fc", 2.5), rtol=1e-12, atol=1e-12)
+    g1, g2 = {}, {}
+    np.testing.assert_allclose(mx._mx_lin_bwd(x, dy, lin, ad, "fc", 2.5, g1), so._lin_bwd(x, dy, lin, ad, "fc", 2.5, g2),
+                               rtol=1e-12, atol=1e-9)
+    for k in (0, 1):
+        np.testing.assert_allclose(g1["fc"][k], g2["fc"][k], rtol=1e-12, atol=1e-9)
