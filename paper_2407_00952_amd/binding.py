@@ -19,7 +19,7 @@ SLORA_OK, SLORA_EINVAL, SLORA_ESTATE, SLORA_ENOSPC, SLORA_EHIP, SLORA_EZERO = 0,
 PROJ = {"q": 0, "k": 1, "v": 2, "o": 3, "fc": 4, "pr": 5}
 FROZEN = {"ln1_g": 0, "ln1_b": 1, "Wqkv": 2, "bqkv": 3, "Wo": 4, "bo": 5, "ln2_g": 6, "ln2_b": 7,
           "Wfc": 8, "bfc": 9, "Wpr": 10, "bpr": 11}
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_MXFP8 = 0, 1, 2
 MAX_RANK, MAX_CLIENTS = 16, 64
 
 EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind_workspace",
@@ -321,7 +321,7 @@ class Server:
 
     blocks / adapters: as produced by synth.make_stack_inputs (numpy float32)."""
 
-    def __init__(self, cfg, blocks, adapters, max_seqs=None):
+    def __init__(self, cfg, blocks, adapters, max_seqs=None, dtype=DTYPE_BF16):
         import torch
         self.cfg = cfg
         mask = 0
@@ -329,7 +329,7 @@ class Server:
             mask |= 1 << PROJ[p]
         self.max_seqs = max_seqs or cfg.n_seq
         self.ctx = slora_create(cfg.d_model, cfg.n_head, cfg.d_ff, len(blocks), cfg.lora_r, cfg.lora_alpha, mask,
-                                self.max_seqs, cfg.seq_len, DTYPE_BF16, cfg.ln_eps)
+                                self.max_seqs, cfg.seq_len, dtype, cfg.ln_eps)
         self.ws_bytes = slora_workspace_bytes(self.ctx)
         self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device="cuda")
         base = self.ws.data_ptr()

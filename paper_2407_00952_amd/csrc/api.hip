@@ -74,7 +74,12 @@ struct BlockWs {
     // saved between forward and backward
     size_t h_in, stats1, qkv, o, o_lo, lse, h_mid, stats2, f, u, u2, g;
     size_t zs[SLORA_NPROJ];
+    // compressed mode: MXFP8 codes / scales of the eight GEMM weight operands (MXW_* below)
+    size_t mxq[8], mxs[8];
 };
+
+// the frozen operand of each of a block's eight GEMMs
+enum { MXW_QKV = 0, MXW_O, MXW_FC, MXW_PR, MXW_QKVT, MXW_OT, MXW_FCT, MXW_PRT };
 
 }  // namespace
 
@@ -90,6 +95,8 @@ struct slora_ctx {
     // transients
     size_t t_u, t_u2, t_g, t_df, t_du2, t_do, t_dqkv, t_du, t_ps, t_delta, t_part;
     size_t t_dh32[2], t_dh16[2];
+    bool mx;                                    // frozen products in MXFP8 (SLORA_DTYPE_MXFP8)
+    size_t t_xq, t_xs;                          // codes / scales of the activation operand of the current GEMM
     size_t shadow_begin, shadow_end, cast_tab, sgd_tab;
     std::vector<CastDesc> h_cast;
     std::vector<SgdDesc> h_sgd;
@@ -123,6 +130,14 @@ void plan_workspace(slora_ctx *c)
         b.WoT = take(2 * d * d);
         b.WfcT = take(2 * d * dff);
         b.WprT = take(2 * dff * d);
+        if (c->mx) {
+            // [N,K] of each operand: Wqkv [3d,d], Wo [d,d], Wfc [dff,d], Wpr [d,dff] and their transposes
+            const size_t nk[8][2] = {{3 * d, d}, {d, d}, {dff, d}, {d, dff}, {d, 3 * d}, {d, d}, {d, dff}, {dff, d}};
+            for (int i = 0; i < 8; ++i) {
+                b.mxq[i] = take(nk[i][0] * nk[i][1]);
+                b.mxs[i] = take(nk[i][0] * nk[i][1] / 32);
+            }
+        }
     }
     c->shadow_begin = off;
     for (int l = 0; l < c->L; ++l) {
@@ -176,6 +191,12 @@ void plan_workspace(slora_ctx *c)
     c->t_ps = take(2 * T * 64);
     c->t_delta = take(4 * T * H);
     c->t_part = take(4 * lora_grad_partial_floats(c->maxT, (int)(dff > d ? dff : d)));
+    c->t_xq = c->t_xs = 0;
+    if (c->mx) {
+        const size_t kmax = dff > 3 * d ? dff : 3 * d;
+        c->t_xq = take(T * kmax);
+        c->t_xs = take(T * kmax / 32);
+    }
     for (int i = 0; i < 2; ++i) {
         c->t_dh32[i] = take(4 * T * d);
         c->t_dh16[i] = take(2 * T * d);
@@ -249,6 +270,16 @@ int prepare(slora_ctx *c, hipStream_t st)
         if ((rc = launch_transpose_bf16(fz[SLORA_WO], c->d, c->d, at<bf16>(c, b.WoT), st))) return rc;
         if ((rc = launch_transpose_bf16(fz[SLORA_WFC], c->dff, c->d, at<bf16>(c, b.WfcT), st))) return rc;
         if ((rc = launch_transpose_bf16(fz[SLORA_WPR], c->d, c->dff, at<bf16>(c, b.WprT), st))) return rc;
+        if (c->mx) {
+            const int d = c->d, dff = c->dff;
+            const bf16 *w[8] = {fz[SLORA_WQKV], fz[SLORA_WO], fz[SLORA_WFC], fz[SLORA_WPR], at<bf16>(c, b.WqkvT),
+                                at<bf16>(c, b.WoT), at<bf16>(c, b.WfcT), at<bf16>(c, b.WprT)};
+            const int nk[8][2] = {{3 * d, d}, {d, d}, {dff, d}, {d, dff}, {d, 3 * d}, {d, d}, {d, dff}, {dff, d}};
+            for (int i = 0; i < 8; ++i)
+                if ((rc = launch_mx_quantize(w[i], nk[i][1], nk[i][0], nk[i][1], at<unsigned char>(c, b.mxq[i]),
+                                             at<unsigned char>(c, b.mxs[i]), st)))
+                    return rc;
+        }
     }
     c->prepared = true;
     c->shadows_dirty = true;
@@ -278,6 +309,17 @@ GemmArgs gemm_base(const bf16 *X, int ldx, const bf16 *W, int M, int N, int K, c
     a.X = X; a.ldx = ldx; a.W = W; a.ldw = K; a.M = M; a.N = N; a.K = K;
     a.nseg = 1; a.seg_n = N; a.bias = bias; a.ldo = N; a.zscale = s; a.K2 = 16; a.ldz = K; a.ldt = 32;
     return a;
+}
+
+// compressed mode: point a GEMM at the packed form of its frozen operand and at the conversion scratch
+inline void set_mx(const slora_ctx *c, int l, int which, GemmArgs &a, MxOperands &m)
+{
+    if (!c->mx) return;
+    m.wq = at<unsigned char>(c, c->bw[l].mxq[which]);
+    m.ws = at<unsigned char>(c, c->bw[l].mxs[which]);
+    m.xq = at<unsigned char>(c, c->t_xq);
+    m.xs = at<unsigned char>(c, c->t_xs);
+    a.mx = &m;
 }
 
 int lora_grads(slora_ctx *c, int l, int p, const bf16 *x, int ldx, const bf16 *dy, int ldy_, const bf16 *ps, int ldps,
@@ -324,7 +366,8 @@ int slora_create(const slora_config *cfg, slora_ctx **out)
 {
     if (!cfg || !out) return SLORA_EINVAL;
     *out = nullptr;
-    if (cfg->dtype != SLORA_DTYPE_BF16) return SLORA_EINVAL;
+    if (cfg->dtype != SLORA_DTYPE_BF16 && cfg->dtype != SLORA_DTYPE_MXFP8) return SLORA_EINVAL;
+    if (cfg->dtype == SLORA_DTYPE_MXFP8 && ((cfg->d_model % 128) || (cfg->d_ff % 128))) return SLORA_EINVAL;
     if (cfg->d_model <= 0 || cfg->n_head <= 0 || cfg->d_model % 64 || cfg->d_model != cfg->n_head * 64)
         return SLORA_EINVAL;
     if (cfg->d_model > 2048) return SLORA_EINVAL;
@@ -342,6 +385,7 @@ int slora_create(const slora_config *cfg, slora_ctx **out)
     c->S = cfg->seq_len; c->maxT = cfg->max_seqs * cfg->seq_len;
     c->s = cfg->lora_alpha / (float)cfg->lora_r;
     c->mask = cfg->lora_mask;
+    c->mx = cfg->dtype == SLORA_DTYPE_MXFP8;
     c->n_qkv = 0;
     for (int p = 0; p < 3; ++p) c->qkv_idx[p] = adapted(c, p) ? c->n_qkv++ : -1;
     c->nz_qkv = 16 * c->n_qkv;
@@ -431,6 +475,8 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                     a.zmat[p] = at<bf16>(c, b.fz[p]); a.tmat[p] = at<bf16>(c, b.ft[p]);
                     a.zspill[p] = at<bf16>(c, b.zs[p]);
                 }
+            MxOperands mxo;
+            set_mx(c, l, MXW_QKV, a, mxo);
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? 16 : 0, st))) return rc;
         }
         if ((rc = launch_attn_fwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<bf16>(c, b.o_lo), at<float>(c, b.lse), c->n_seq,
@@ -446,6 +492,8 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                 a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_O]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_O]);
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_O]);
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_O, a, mxo);
             if ((rc = launch_gemm(a, EPI_RESID, ad ? 16 : 0, st))) return rc;
         }
         bf16 *u2 = at<bf16>(c, b.u2 ? b.u2 : c->t_u2);
@@ -462,6 +510,8 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                 a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_FC]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_FC]);
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_FC]);
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_FC, a, mxo);
             if ((rc = launch_gemm(a, EPI_GELU, ad ? 16 : 0, st))) return rc;
         }
         // h'' = h' + g Wpr^T + bpr (+ adapter): next block's input, or y for the last block
@@ -475,6 +525,8 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                 a.zmat[0] = at<bf16>(c, b.fz[SLORA_PROJ_PR]); a.tmat[0] = at<bf16>(c, b.ft[SLORA_PROJ_PR]);
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_PR]);
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_PR, a, mxo);
             if ((rc = launch_gemm(a, EPI_RESID, ad ? 16 : 0, st))) return rc;
         }
     }
@@ -563,6 +615,8 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_PR]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_PR]);
                 a.zspill[0] = ps;
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_PRT, a, mxo);
             if ((rc = launch_gemm(a, EPI_DGELU, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_PR, at<bf16>(c, b.g), dff, dh2_16, d, ps, SL_RP, st)))
                 return rc;
@@ -577,6 +631,8 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_FC]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_FC]);
                 a.zspill[0] = ps;
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_FCT, a, mxo);
             if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_FC, at<bf16>(c, b.u2), d, df, dff, ps, SL_RP, st))) return rc;
         }
@@ -596,6 +652,8 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zmat[0] = at<bf16>(c, b.bz[SLORA_PROJ_O]); a.tmat[0] = at<bf16>(c, b.bt[SLORA_PROJ_O]);
                 a.zspill[0] = ps;
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_OT, a, mxo);
             if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_O, at<bf16>(c, b.o), d, dh1_16, d, ps, SL_RP, st))) return rc;
         }
@@ -613,6 +671,8 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zmat[0] = at<bf16>(c, b.bz_qkv); a.tmat[0] = at<bf16>(c, b.bt_qkv); a.zspill[0] = ps;
                 a.K2 = c->k2_qkv; a.ldt = c->k2p_qkv;
             }
+            MxOperands mxo;
+            set_mx(c, l, MXW_QKVT, a, mxo);
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? c->nz_qkv : 0, st))) return rc;
             // dB per adapted projection (its own slice of dq|dk|dv against its own zs); dA for the adapters
             // two at a time: they share the operand u, and their rank-space gradients sit side by side in ps

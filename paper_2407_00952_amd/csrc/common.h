@@ -64,6 +64,13 @@ struct EmbedSrc {
 // ---- GEMM ---------------------------------------------------------------------------------
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_DGELU = 3 };
 
+// Compressed mode of a context: the frozen operand of a GEMM as MXFP8 codes + block scales (packed once),
+// and scratch for the codes + scales of its activation operand, which is converted right before the launch.
+struct MxOperands {
+    const unsigned char *wq, *ws;    // [N,K] element codes, [N,K/32] scale codes
+    unsigned char *xq, *xs;          // scratch [M,K], [M,K/32]
+};
+
 struct GemmArgs {
     const bf16 *X; int ldx;          // [M,K]
     const bf16 *W; int ldw;          // [N,K]  (N = nseg * seg_n)
@@ -77,9 +84,15 @@ struct GemmArgs {
     int K2; float zscale;            // K2 = NZ
     // epilogue
     void *out0; void *out1; const void *aux; int ldo;
+    const MxOperands *mx;            // null: bf16 product.  Else: the product runs on the fp8 matrix cores
 };
 
 int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);
+// the same call with the frozen product in MXFP8 (a.mx set): converts X, forms the rank-space activations
+// of the adapted segments with a separate projection kernel (into a.zspill), then one fp8 GEMM launch
+int launch_gemm_mx_stack(const GemmArgs &a, int epi, int nz, hipStream_t st);
+int launch_mx_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned char *codes, unsigned char *scales,
+                       hipStream_t st);
 
 // ---- elementwise / norm / attention / lora-grad launchers ---------------------------------------
 int launch_ln_fwd(const float *h_f32, const ClientTable *gather /*null unless block 0*/, float *h_copy,

@@ -390,6 +390,7 @@ static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
     if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K % BK) != 0 || a.nseg < 1 || a.nseg > 3 ||
         a.nseg * a.seg_n != a.N || (a.ldx % 8) || (a.ldw % 8) || (a.seg_n % 8) || (a.ldo % 8))
         return -1;
+    if (a.mx) return launch_gemm_mx_stack(a, epi, nz, st);
     // the copies address both operands with 32-bit byte offsets from their bases
     if ((unsigned long long)a.M * a.ldx * 2ull >= (1ull << 32) || (unsigned long long)a.N * a.ldw * 2ull >= (1ull << 32))
         return -1;

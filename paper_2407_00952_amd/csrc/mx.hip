@@ -553,6 +553,38 @@ bool mx_lin_args_ok(int T, int n_in, int n_out, int r)
 
 }  // namespace
 
+int launch_mx_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned char *codes, unsigned char *scales,
+                       hipStream_t st)
+{
+    if (M <= 0 || K <= 0 || (K % 32) || ldx < K) return -1;
+    return launch_quantize(x, ldx, M, K, codes, scales, st);
+}
+
+int launch_gemm_mx_stack(const GemmArgs &g, int epi, int nz, hipStream_t st)
+{
+    const MxOperands &m = *g.mx;
+    if ((g.K % 128) || (g.seg_n % 8) || g.ldw != g.K || !m.wq || !m.ws || !m.xq || !m.xs) return -1;
+    if ((unsigned long long)g.M * g.K >= (1ull << 32) || (unsigned long long)g.N * g.K >= (1ull << 32)) return -1;
+    int rc;
+    if ((rc = launch_quantize(g.X, g.ldx, g.M, g.K, m.xq, m.xs, st))) return rc;
+    MxArgs a = mx_plain(m.xq, m.xs, m.wq, m.ws, g.bias, g.out0, g.M, g.N, g.K);
+    a.nseg = g.nseg; a.seg_n = g.seg_n;
+    a.out1 = g.out1; a.aux = g.aux; a.ldo = g.ldo;
+    if (nz > 0) {
+        a.K2 = g.K2; a.ldt = g.ldt;
+        for (int sgm = 0; sgm < g.nseg; ++sgm) {
+            if (!g.zmat[sgm]) continue;
+            // the bf16 kernel forms these inside its K loop from the bf16 tile; here the tile is fp8
+            if (!g.zspill[sgm] || !g.tmat[sgm]) return -1;
+            if ((rc = launch_rank_project(g.X, g.ldx, g.M, g.K, g.zmat[sgm], g.ldz, nz, g.zscale, g.zspill[sgm], st)))
+                return rc;
+            a.zs[sgm] = g.zspill[sgm];
+            a.tmat[sgm] = g.tmat[sgm];
+        }
+    }
+    return launch_gemm_mx(a, st, false, epi);
+}
+
 int slora_mx_quantize(int64_t M, int32_t K, const void *x, int64_t ldx, void *codes, void *scales, void *stream)
 {
     if (M <= 0 || K <= 0 || (K % 32) || ldx < K || (ldx % 8) || !x || !codes || !scales) return SLORA_EINVAL;

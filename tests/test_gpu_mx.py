@@ -367,3 +367,59 @@ def test_linear_w4_full_code_range():
     colerr = np.abs(got - ref).max(axis=0) / np.abs(ref).max(axis=0)
     say("   max-norm relative error %.2e (worst column %.2e)" % (e, colerr.max()))
     assert e <= MX_TOL and colerr.max() <= 2 * MX_TOL
+
+
+MX_STACKS = {
+    "qv-r4": synth.tiny_config(d_model=128, n_head=2, d_ff=256, n_blocks=2, lora_r=4, lora_proj=("q", "v"),
+                               n_clients=2, batch=2, seq_len=128, seed=synth.BASE_SEED + 301),
+    "all-proj-r8": synth.tiny_config(d_model=256, n_head=4, d_ff=512, n_blocks=2, lora_r=8,
+                                     lora_proj=synth.PROJ_NAMES, n_clients=3, batch=1, seq_len=64,
+                                     seed=synth.BASE_SEED + 302),
+    "no-adapters": synth.tiny_config(d_model=128, n_head=2, d_ff=384, n_blocks=1, lora_r=4, lora_proj=(),
+                                     n_clients=1, batch=3, seq_len=192, seed=synth.BASE_SEED + 303),
+    "k-o-pr-r3": synth.tiny_config(d_model=384, n_head=6, d_ff=640, n_blocks=3, lora_r=3, lora_proj=("k", "o", "pr"),
+                                   n_clients=2, batch=1, seq_len=64, seed=synth.BASE_SEED + 304),
+}
+# Both sides convert bf16 tensors that agree to about 2^-9; an element near a rounding boundary then lands on
+# the neighbouring code (a step of 2^-4 .. 2^-3 of its value) on one side only: about 2 % of the elements of
+# every operand, i.e. an extra relative error of ~1 % rms per product, which accumulates over the 8 products of
+# a block in each direction.  Observed worst case 2.7e-2 (three blocks, adapter gradients); the bound leaves
+# a factor 2.
+MX_STACK_TOL = 5e-2
+
+
+@pytest.mark.parametrize("name", list(MX_STACKS))
+def test_stack_with_mxfp8_frozen_products(name):
+    import torch
+    from gpu_util import gpu_round
+    cfg = MX_STACKS[name]
+    say("mxfp8 stack", name)
+    inp = synth.make_stack_inputs(cfg)
+    n_seq = sum(c.shape[0] for c in inp["clients"])
+    srv = B.Server(cfg, inp["blocks"], inp["adapters"], max_seqs=n_seq, dtype=B.DTYPE_MXFP8)
+    srv, Y, dX, grads = gpu_round(cfg, inp, server=srv)
+    orc = mx.make_mx_server_oracle(inp["blocks"], inp["adapters"], cfg.n_head, cfg.lora_alpha, cfg.lora_r, cfg.ln_eps)
+    Yo = orc.fwd(inp["clients"]); dXo = orc.bwd(inp["dY"])
+    e = {"Y": relerr(Y, Yo)}
+    for i, (a, b) in enumerate(zip(dX, dXo)):
+        e["dx%d" % i] = relerr(a, b)
+    for l, gl in enumerate(orc.grads):
+        for p, (dA, dB) in gl.items():
+            e["dA[%d,%s]" % (l, p)] = relerr(grads[l][p][0], dA)
+            e["dB[%d,%s]" % (l, p)] = relerr(grads[l][p][1], dB)
+    top = sorted(e.items(), key=lambda kv: -kv[1])[:5]
+    say("   worst: " + ", ".join("%s=%.2e" % kv for kv in top))
+    assert max(e.values()) <= MX_STACK_TOL, e
+    # and it IS a different model from the uncompressed one: the adapter gradients (which see the products'
+    # noise undiluted by the residual stream) are further from the exact oracle's than from their own
+    from gpu_util import oracle_of
+    exact = oracle_of(cfg, inp)
+    exact.fwd(inp["clients"]); exact.bwd(inp["dY"])
+    far, near = 0.0, 0.0
+    for l, gl in enumerate(exact.grads):
+        for p, (dA, dB) in gl.items():
+            far = max(far, relerr(grads[l][p][0], dA), relerr(grads[l][p][1], dB))
+            near = max(near, e["dA[%d,%s]" % (l, p)], e["dB[%d,%s]" % (l, p)])
+    say("   adapter gradients: %.2e from the compressed oracle, %.2e from the uncompressed one" % (near, far))
+    if cfg.lora_proj:
+        assert far > 1.5 * near
