@@ -97,6 +97,8 @@ struct slora_ctx {
     size_t t_dh32[2], t_dh16[2];
     bool mx;                                    // frozen products in MXFP8 (SLORA_DTYPE_MXFP8)
     size_t t_xq, t_xs;                          // codes / scales of the activation operand of the current GEMM
+    size_t t_qa, t_qas, t_qb, t_qbs;            // codes / scales written by producers: [T,d] (LayerNorm outputs and
+                                                // gradients), [T,dff] (GELU output, its gradient)
     size_t shadow_begin, shadow_end, cast_tab, sgd_tab;
     std::vector<CastDesc> h_cast;
     std::vector<SgdDesc> h_sgd;
@@ -191,11 +193,15 @@ void plan_workspace(slora_ctx *c)
     c->t_ps = take(2 * T * 64);
     c->t_delta = take(4 * T * H);
     c->t_part = take(4 * lora_grad_partial_floats(c->maxT, (int)(dff > d ? dff : d)));
-    c->t_xq = c->t_xs = 0;
+    c->t_xq = c->t_xs = c->t_qa = c->t_qas = c->t_qb = c->t_qbs = 0;
     if (c->mx) {
         const size_t kmax = dff > 3 * d ? dff : 3 * d;
         c->t_xq = take(T * kmax);
         c->t_xs = take(T * kmax / 32);
+        c->t_qa = take(T * d);
+        c->t_qas = take(T * d / 32);
+        c->t_qb = take(T * dff);
+        c->t_qbs = take(T * dff / 32);
     }
     for (int i = 0; i < 2; ++i) {
         c->t_dh32[i] = take(4 * T * d);
@@ -312,15 +318,21 @@ GemmArgs gemm_base(const bf16 *X, int ldx, const bf16 *W, int M, int N, int K, c
 }
 
 // compressed mode: point a GEMM at the packed form of its frozen operand and at the conversion scratch
-inline void set_mx(const slora_ctx *c, int l, int which, GemmArgs &a, MxOperands &m)
+// `ready`: 0 = convert X into the scratch; 1 = its producer wrote the codes into the [T,d] buffer; 2 = into the
+// [T,dff] buffer
+inline void set_mx(const slora_ctx *c, int l, int which, GemmArgs &a, MxOperands &m, int ready = 0)
 {
     if (!c->mx) return;
     m.wq = at<unsigned char>(c, c->bw[l].mxq[which]);
     m.ws = at<unsigned char>(c, c->bw[l].mxs[which]);
-    m.xq = at<unsigned char>(c, c->t_xq);
-    m.xs = at<unsigned char>(c, c->t_xs);
+    m.xq = at<unsigned char>(c, ready == 1 ? c->t_qa : ready == 2 ? c->t_qb : c->t_xq);
+    m.xs = at<unsigned char>(c, ready == 1 ? c->t_qas : ready == 2 ? c->t_qbs : c->t_xs);
+    m.x_ready = ready != 0;
     a.mx = &m;
 }
+// the producers' code outputs (null outside the compressed mode)
+inline unsigned char *qa(const slora_ctx *c) { return c->mx ? at<unsigned char>(c, c->t_qa) : nullptr; }
+inline unsigned char *qas(const slora_ctx *c) { return c->mx ? at<unsigned char>(c, c->t_qas) : nullptr; }
 
 int lora_grads(slora_ctx *c, int l, int p, const bf16 *x, int ldx, const bf16 *dy, int ldy_, const bf16 *ps, int ldps,
                hipStream_t st)
@@ -464,7 +476,7 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
         // LN1 (block 0 gathers the clients' activations: S = [s_1; ...; s_N], or looks the embedding up)
         if ((rc = launch_ln_fwd(l == 0 ? nullptr : h_in, l == 0 ? tabp : nullptr, h_in, fz[SLORA_LN1_G],
                                 fz[SLORA_LN1_B], c->cfg.ln_eps, u, at<float>(c, b.stats1), T, d, st,
-                                l == 0 ? emb : nullptr)))
+                                l == 0 ? emb : nullptr, qa(c), qas(c))))
             return rc;
         // q | k | v = u Wqkv^T + b (+ adapters)
         {
@@ -476,7 +488,7 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                     a.zspill[p] = at<bf16>(c, b.zs[p]);
                 }
             MxOperands mxo;
-            set_mx(c, l, MXW_QKV, a, mxo);
+            set_mx(c, l, MXW_QKV, a, mxo, 1);
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? 16 : 0, st))) return rc;
         }
         if ((rc = launch_attn_fwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<bf16>(c, b.o_lo), at<float>(c, b.lse), c->n_seq,
@@ -498,7 +510,7 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
         }
         bf16 *u2 = at<bf16>(c, b.u2 ? b.u2 : c->t_u2);
         if ((rc = launch_ln_fwd(at<float>(c, b.h_mid), nullptr, nullptr, fz[SLORA_LN2_G], fz[SLORA_LN2_B],
-                                c->cfg.ln_eps, u2, at<float>(c, b.stats2), T, d, st)))
+                                c->cfg.ln_eps, u2, at<float>(c, b.stats2), T, d, st, nullptr, qa(c), qas(c))))
             return rc;
         // f = u2 Wfc^T + bfc (+ adapter); g = GELU(f); the slot `f` keeps GELU'(f), all the backward needs
         bf16 *g = at<bf16>(c, b.g ? b.g : c->t_g);
@@ -511,7 +523,8 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_FC]);
             }
             MxOperands mxo;
-            set_mx(c, l, MXW_FC, a, mxo);
+            set_mx(c, l, MXW_FC, a, mxo, 1);
+            if (c->mx) { a.oq = at<unsigned char>(c, c->t_qb); a.os = at<unsigned char>(c, c->t_qbs); }   // codes of g
             if ((rc = launch_gemm(a, EPI_GELU, ad ? 16 : 0, st))) return rc;
         }
         // h'' = h' + g Wpr^T + bpr (+ adapter): next block's input, or y for the last block
@@ -526,7 +539,7 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
                 a.zspill[0] = at<bf16>(c, b.zs[SLORA_PROJ_PR]);
             }
             MxOperands mxo;
-            set_mx(c, l, MXW_PR, a, mxo);
+            set_mx(c, l, MXW_PR, a, mxo, 2);
             if ((rc = launch_gemm(a, EPI_RESID, ad ? 16 : 0, st))) return rc;
         }
     }
@@ -602,6 +615,9 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
     // gradient of the residual stream entering the block from above: fp32 (+ bf16 GEMM operand)
     const float *dh2_32 = nullptr;
     const bf16 *dh2_16 = (const bf16 *)dy;
+    // compressed mode: the gradient entering a block is also held as codes (written by the LayerNorm backward
+    // of the block above; for the caller's dY by one conversion pass here)
+    if (c->mx && (rc = launch_mx_quantize(dh2_16, d, T, d, qa(c), qas(c), st))) return rc;
     for (int l = c->L - 1; l >= 0; --l) {
         const BlockWs &b = c->bw[l];
         const auto &fz = c->frozen[l];
@@ -616,7 +632,8 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zspill[0] = ps;
             }
             MxOperands mxo;
-            set_mx(c, l, MXW_PRT, a, mxo);
+            set_mx(c, l, MXW_PRT, a, mxo, 1);
+            if (c->mx) { a.oq = at<unsigned char>(c, c->t_qb); a.os = at<unsigned char>(c, c->t_qbs); }   // codes of df
             if ((rc = launch_gemm(a, EPI_DGELU, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_PR, at<bf16>(c, b.g), dff, dh2_16, d, ps, SL_RP, st)))
                 return rc;
@@ -632,7 +649,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zspill[0] = ps;
             }
             MxOperands mxo;
-            set_mx(c, l, MXW_FCT, a, mxo);
+            set_mx(c, l, MXW_FCT, a, mxo, 2);
             if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_FC, at<bf16>(c, b.u2), d, df, dff, ps, SL_RP, st))) return rc;
         }
@@ -640,7 +657,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
         float *dh1_32 = at<float>(c, c->t_dh32[1]);
         bf16 *dh1_16 = at<bf16>(c, c->t_dh16[1]);
         if ((rc = launch_ln_bwd(du2, at<float>(c, b.h_mid), at<float>(c, b.stats2), fz[SLORA_LN2_G], dh2_32,
-                                dh2_32 ? nullptr : dh2_16, dh1_32, dh1_16, nullptr, T, d, st)))
+                                dh2_32 ? nullptr : dh2_16, dh1_32, dh1_16, nullptr, T, d, st, qa(c), qas(c))))
             return rc;
         // do = dh' Wo (+ adapter)
         bf16 *dob = at<bf16>(c, c->t_do);
@@ -653,7 +670,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
                 a.zspill[0] = ps;
             }
             MxOperands mxo;
-            set_mx(c, l, MXW_OT, a, mxo);
+            set_mx(c, l, MXW_OT, a, mxo, 1);
             if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_O, at<bf16>(c, b.o), d, dh1_16, d, ps, SL_RP, st))) return rc;
         }
@@ -703,7 +720,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
         bf16 *nx16 = at<bf16>(c, c->t_dh16[0]);
         if (l > 0) {
             if ((rc = launch_ln_bwd(dub, at<float>(c, b.h_in), at<float>(c, b.stats1), fz[SLORA_LN1_G], dh1_32,
-                                    nullptr, nx32, nx16, nullptr, T, d, st)))
+                                    nullptr, nx32, nx16, nullptr, T, d, st, qa(c), qas(c))))
                 return rc;
             dh2_32 = nx32;
             dh2_16 = nx16;

@@ -68,7 +68,8 @@ enum { EPI_STORE = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_DGELU = 3 };
 // and scratch for the codes + scales of its activation operand, which is converted right before the launch.
 struct MxOperands {
     const unsigned char *wq, *ws;    // [N,K] element codes, [N,K/32] scale codes
-    unsigned char *xq, *xs;          // scratch [M,K], [M,K/32]
+    unsigned char *xq, *xs;          // [M,K], [M,K/32]: conversion scratch, or (x_ready) codes a producer wrote
+    int x_ready;                     // the kernel that produced X also wrote its codes: no conversion pass
 };
 
 struct GemmArgs {
@@ -85,6 +86,10 @@ struct GemmArgs {
     // epilogue
     void *out0; void *out1; const void *aux; int ldo;
     const MxOperands *mx;            // null: bf16 product.  Else: the product runs on the fp8 matrix cores
+    // compressed mode only: also write the bf16 tensor of the epilogue (GELU: out1, DGELU: out0) as MXFP8
+    // codes [M,ldo] + scales [M,ldo/32], so that the product that consumes it needs no conversion pass
+    unsigned char *oq, *os;
+    static constexpr bool kEmitCodes = false;   // the bf16 kernel never does
 };
 
 int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);
@@ -97,10 +102,12 @@ int launch_mx_quantize(const bf16 *x, long long ldx, long long M, int K, unsigne
 // ---- elementwise / norm / attention / lora-grad launchers ---------------------------------------
 int launch_ln_fwd(const float *h_f32, const ClientTable *gather /*null unless block 0*/, float *h_copy,
                   const bf16 *gamma, const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d,
-                  hipStream_t st, const EmbedSrc *embed = nullptr);
+                  hipStream_t st, const EmbedSrc *embed = nullptr, unsigned char *u_codes = nullptr,
+                  unsigned char *u_scales = nullptr);   // optional MXFP8 copy of u (d a multiple of 32)
 int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16 *gamma,
                   const float *dres_f32, const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16,
-                  const ClientTable *scatter, int T, int d, hipStream_t st);
+                  const ClientTable *scatter, int T, int d, hipStream_t st, unsigned char *o_codes = nullptr,
+                  unsigned char *o_scales = nullptr);   // optional MXFP8 copy of out_bf16
 int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st);
 int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16 *dout, const float *lse,
                     float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st);

@@ -3,6 +3,7 @@
 // out0, out1, aux and ldo with the meaning given at GemmArgs.
 #pragma once
 #include "common.h"
+#include "mx_codec.h"
 
 // Epilogue operands that come from global memory (the residual stream, or the saved GELU derivative),
 // fetched one 32-row strip ahead of their use so that their latency hides behind the LDS transpose.
@@ -27,6 +28,30 @@ __device__ __forceinline__ void load_aux(const Args &a, int row, int col, bool o
         for (int i = 0; i < 8; ++i) x.f[i] = f2bf(0.f);
         if (ok) x.f = *(const bf16x8 *)((const bf16 *)a.aux + (size_t)row * a.ldo + col);
     }
+}
+
+// MXFP8 copy of 8 consecutive bf16 outputs (compressed mode): the 4 lanes that hold a block of 32 columns are
+// neighbours and are active together (column limits are multiples of 32 there), two shuffles give the block maximum.
+template <class Args>
+__device__ __forceinline__ void store_codes8(const Args &a, int row, int col, bf16x8 w)
+{
+    union { bf16x8 v; unsigned short s[8]; } bits;       // the eight bit patterns
+    bits.v = w;
+    unsigned hb[8], mag = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        hb[i] = bits.s[i];
+        mag = max(mag, hb[i] & 0x7FFFu);
+    }
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
+    const int scode = mx_scale_code(mag);
+    unsigned q[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        q[i] = mx_encode_pair_bf16(hb[4 * i], hb[4 * i + 1], scode) | (mx_encode_pair_bf16(hb[4 * i + 2], hb[4 * i + 3], scode) << 16);
+    *(uint2 *)(a.oq + (size_t)row * a.ldo + col) = make_uint2(q[0], q[1]);
+    if ((col & 31) == 0) a.os[(size_t)row * (a.ldo >> 5) + (col >> 5)] = (unsigned char)scode;
 }
 
 // Epilogue on 8 consecutive columns of one output row (v already holds acc + bias).
@@ -64,10 +89,16 @@ __device__ __forceinline__ void store_row8(const Args &a, int row, int col, floa
         }
         *(bf16x8 *)((bf16 *)a.out0 + o) = wf;
         *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
+        if constexpr (Args::kEmitCodes) {
+            if (a.oq) store_codes8(a, row, col, wg);
+        }
     } else {   // EPI_DGELU
         bf16x8 w;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * bf2f(x.f[i]));   // aux holds GELU'(f)
         *(bf16x8 *)((bf16 *)a.out0 + o) = w;
+        if constexpr (Args::kEmitCodes) {
+            if (a.oq) store_codes8(a, row, col, w);
+        }
     }
 }

@@ -32,17 +32,17 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 // ------------------------------------------------------------------------------------------------
 
 // Each thread converts 8 consecutive elements of a row; 4 neighbouring threads form a block of 32.
-__global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict__ x, long long ldx, long long M, int K,
+// Grid: x = row, y = 128-chunk slice of the row (no index division: the kernel is ALU-bound, not HBM-bound).
+__global__ __launch_bounds__(128) void mx_quantize_kernel(const bf16 *__restrict__ x, long long ldx, long long M, int K,
                                                           unsigned char *__restrict__ codes,
                                                           unsigned char *__restrict__ scales)
 {
     const int cpr = K >> 3;                              // 16-byte chunks per row
-    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool live = t < M * cpr;
-    const long long row = live ? t / cpr : 0;
-    const int ch = live ? (int)(t - row * cpr) : 0;
+    const long long row = blockIdx.x;
+    const int ch = blockIdx.y * 128 + threadIdx.x;
+    const bool live = ch < cpr;
     uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-    if (live) raw = *(const uint4 *)(x + row * ldx + ch * 8);
+    if (live) raw = *(const uint4 *)(x + row * ldx + ch * 8);   // (M is the grid's x extent)
     const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
     // largest magnitude of the block, compared on the bit patterns (monotone for finite values)
     unsigned mag = 0;
@@ -56,10 +56,8 @@ __global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict
     const int scode = mx_scale_code(mag);
     unsigned out[2] = {0u, 0u};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const unsigned h = (i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu);
-        out[i >> 2] |= mx_encode_bf16(h, scode) << (8 * (i & 3));
-    }
+    for (int i = 0; i < 4; ++i)                           // w[i] holds elements 2i (low half) and 2i + 1
+        out[i >> 1] |= mx_encode_pair_bf16(w[i] & 0xFFFFu, w[i] >> 16, scode) << (16 * (i & 1));
     if (live) {
         *(uint2 *)(codes + row * (long long)K + ch * 8) = make_uint2(out[0], out[1]);
         if ((ch & 3) == 0) scales[row * (long long)(K >> 5) + (ch >> 2)] = (unsigned char)scode;
@@ -68,15 +66,14 @@ __global__ __launch_bounds__(256) void mx_quantize_kernel(const bf16 *__restrict
 
 // The same for FP4 E2M1 elements (frozen weights): emax 2, so the scale code is the biased exponent - 2;
 // two codes per byte, the element with the even index in the low nibble.
-__global__ __launch_bounds__(256) void mx_quantize_fp4_kernel(const bf16 *__restrict__ x, long long ldx, long long M,
+__global__ __launch_bounds__(128) void mx_quantize_fp4_kernel(const bf16 *__restrict__ x, long long ldx, long long M,
                                                               int K, unsigned char *__restrict__ codes,
                                                               unsigned char *__restrict__ scales)
 {
-    const int cpr = K >> 3;
-    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool live = t < M * cpr;
-    const long long row = live ? t / cpr : 0;
-    const int ch = live ? (int)(t - row * cpr) : 0;
+    const int cpr = K >> 3;                              // 16-byte chunks per row
+    const long long row = blockIdx.x;
+    const int ch = blockIdx.y * 128 + threadIdx.x;
+    const bool live = ch < cpr;
     uint4 raw = make_uint4(0u, 0u, 0u, 0u);
     if (live) raw = *(const uint4 *)(x + row * ldx + ch * 8);
     const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -143,6 +140,8 @@ struct MxArgs {
     int K2, ldt;
     // epilogue (meaning as in GemmArgs)
     void *out0; void *out1; const void *aux; int ldo;
+    unsigned char *oq, *os;          // optional MXFP8 copy of the epilogue's bf16 tensor (see GemmArgs)
+    static constexpr bool kEmitCodes = true;
 };
 // With W4 the weight operand is MXFP4: W holds two E2M1 codes per byte ([N, K/2]), a tile row is 64 bytes
 // per slab, the lane's 32 elements are 16 consecutive bytes (k = 32g .. 32g+31) and the upper half of the
@@ -449,9 +448,8 @@ inline size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
 int launch_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned char *codes, unsigned char *scales,
                     hipStream_t st)
 {
-    const long long threads = M * (K / 8);
-    hipLaunchKernelGGL(mx_quantize_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, x, ldx, M, K,
-                       codes, scales);
+    hipLaunchKernelGGL(mx_quantize_kernel, dim3((unsigned)M, (unsigned)((K / 8 + 127) / 128)), dim3(128), 0, st, x, ldx,
+                       M, K, codes, scales);
     SL_CHECK_LAUNCH("mx_quantize");
     return 0;
 }
@@ -489,6 +487,7 @@ MxArgs mx_plain(const void *xq, const void *xs, const void *wq, const void *ws, 
     for (int i = 0; i < 3; ++i) { a.zs[i] = nullptr; a.tmat[i] = nullptr; }
     a.K2 = 16; a.ldt = 32;
     a.out0 = y; a.out1 = nullptr; a.aux = nullptr; a.ldo = N;
+    a.oq = nullptr; a.os = nullptr;
     return a;
 }
 
@@ -566,10 +565,14 @@ int launch_gemm_mx_stack(const GemmArgs &g, int epi, int nz, hipStream_t st)
     if ((g.K % 128) || (g.seg_n % 8) || g.ldw != g.K || !m.wq || !m.ws || !m.xq || !m.xs) return -1;
     if ((unsigned long long)g.M * g.K >= (1ull << 32) || (unsigned long long)g.N * g.K >= (1ull << 32)) return -1;
     int rc;
-    if ((rc = launch_quantize(g.X, g.ldx, g.M, g.K, m.xq, m.xs, st))) return rc;
+    if (!m.x_ready && (rc = launch_quantize(g.X, g.ldx, g.M, g.K, m.xq, m.xs, st))) return rc;
     MxArgs a = mx_plain(m.xq, m.xs, m.wq, m.ws, g.bias, g.out0, g.M, g.N, g.K);
     a.nseg = g.nseg; a.seg_n = g.seg_n;
     a.out1 = g.out1; a.aux = g.aux; a.ldo = g.ldo;
+    if (g.oq) {
+        if (!g.os || (g.ldo % 32) || (g.seg_n % 32) || (epi != EPI_GELU && epi != EPI_DGELU)) return -1;
+        a.oq = g.oq; a.os = g.os;
+    }
     if (nz > 0) {
         a.K2 = g.K2; a.ldt = g.ldt;
         for (int sgm = 0; sgm < g.nseg; ++sgm) {
@@ -589,7 +592,7 @@ int slora_mx_quantize(int64_t M, int32_t K, const void *x, int64_t ldx, void *co
 {
     if (M <= 0 || K <= 0 || (K % 32) || ldx < K || (ldx % 8) || !x || !codes || !scales) return SLORA_EINVAL;
     if (!aligned(x, 16) || !aligned(codes, 8)) return SLORA_EINVAL;
-    if ((long long)M * (K / 8) > (1ll << 31) * 256ll) return SLORA_EINVAL;
+    if (M >= (1ll << 31) || K / 8 > 128 * 65535) return SLORA_EINVAL;
     return launch_quantize((const bf16 *)x, ldx, M, K, (unsigned char *)codes, (unsigned char *)scales,
                            (hipStream_t)stream);
 }
@@ -627,9 +630,8 @@ int slora_mx_quantize_fp4(int64_t M, int32_t K, const void *x, int64_t ldx, void
 {
     if (M <= 0 || K <= 0 || (K % 32) || ldx < K || (ldx % 8) || !x || !codes || !scales) return SLORA_EINVAL;
     if (!aligned(x, 16) || !aligned(codes, 4)) return SLORA_EINVAL;
-    const long long threads = (long long)M * (K / 8);
-    if (threads > (1ll << 31) * 256ll) return SLORA_EINVAL;
-    hipLaunchKernelGGL(mx_quantize_fp4_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+    if (M >= (1ll << 31) || K / 8 > 128 * 65535) return SLORA_EINVAL;
+    hipLaunchKernelGGL(mx_quantize_fp4_kernel, dim3((unsigned)M, (unsigned)((K / 8 + 127) / 128)), dim3(128), 0,
                        (hipStream_t)stream, (const bf16 *)x, (long long)ldx, (long long)M, (int)K,
                        (unsigned char *)codes, (unsigned char *)scales);
     SL_CHECK_LAUNCH("mx_quantize_fp4");

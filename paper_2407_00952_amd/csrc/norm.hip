@@ -27,13 +27,41 @@ __device__ __forceinline__ int client_of(const ClientTable &t, int row, int &loc
     return c;
 }
 
+// MXFP8 copy of a row: each lane holds 4 consecutive bf16 values of a 256-column chunk, so a block of 32 columns
+// is 8 neighbouring lanes (three shuffles for its maximum).  Every lane of the wave must call this; lanes
+// whose columns are outside the row (`in_row` false) only take part in the shuffles.
+__device__ __forceinline__ void mx_store_row4(bf16x4 o, bool in_row, int lane, unsigned char *q_row,
+                                              unsigned char *s_row, int col)
+{
+    union { bf16x4 v; unsigned short s[4]; } bits;       // the four bit patterns
+    bits.v = o;
+    unsigned hb[4] = {0u, 0u, 0u, 0u}, mag = 0u;
+    if (in_row) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hb[i] = bits.s[i];
+            mag = max(mag, hb[i] & 0x7FFFu);
+        }
+    }
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
+    mag = max(mag, (unsigned)__shfl_xor((int)mag, 4, 64));
+    const int scode = mx_scale_code(mag);
+    if (in_row) {
+        const unsigned q4 = mx_encode_pair_bf16(hb[0], hb[1], scode) | (mx_encode_pair_bf16(hb[2], hb[3], scode) << 16);
+        *(unsigned *)(q_row + col) = q4;
+        if ((lane & 7) == 0) s_row[col >> 5] = (unsigned char)scode;
+    }
+}
+
 // SRC 0: fp32 rows of h; 1: bf16 rows gathered from the client buffers; 2: embedding lookup;
 // 3: MXFP8 rows (element codes + one scale code per 32 columns) gathered from the client buffers
 template <int SRC>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h, ClientTable tab, EmbedSrc emb,
                                                      float *__restrict__ hcopy, const bf16 *__restrict__ gamma,
                                                      const bf16 *__restrict__ beta, float eps,
-                                                     bf16 *__restrict__ u, float *__restrict__ stats, int T, int d)
+                                                     bf16 *__restrict__ u, float *__restrict__ stats, int T, int d,
+                                                     unsigned char *__restrict__ uq, unsigned char *__restrict__ us)
 {
     constexpr bool GATHER = SRC != 0;
     const int lane = threadIdx.x & 63;
@@ -98,14 +126,18 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int col = c * 256 + lane * 4;
+        bf16x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = f2bf(0.f);
         if (col < d) {
             bf16x4 gm = *(const bf16x4 *)(gamma + col);
             bf16x4 bt = *(const bf16x4 *)(beta + col);
-            bf16x4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = f2bf(v[c][i] * rho * bf2f(gm[i]) + bf2f(bt[i]));
             *(bf16x4 *)(u + (size_t)row * d + col) = o;
         }
+        if (uq != nullptr && c * 256 < d)
+            mx_store_row4(o, col < d, lane, uq + (size_t)row * d, us + (size_t)row * (d >> 5), col);
     }
     if (lane == 0) { stats[2 * row] = mu; stats[2 * row + 1] = rho; }
 }
@@ -118,7 +150,8 @@ template <bool DRES16, int SCATTER>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du, const float *__restrict__ h,
                                                      const float *__restrict__ stats, const bf16 *__restrict__ gamma,
                                                      const void *__restrict__ dres, float *__restrict__ out32,
-                                                     bf16 *__restrict__ out16, ClientTable tab, int T, int d)
+                                                     bf16 *__restrict__ out16, ClientTable tab, int T, int d,
+                                                     unsigned char *__restrict__ oq, unsigned char *__restrict__ os)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -185,27 +218,16 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du
             if (dst16) *(bf16x4 *)(dst16 + col) = o16;
         }
         if (SCATTER == 2) {
-            // every lane of the wave takes part in the shuffles; d is a multiple of 32, so the 8 lanes of a
-            // block are either all inside the row or all outside
-            unsigned hb[4] = {0u, 0u, 0u, 0u}, mag = 0u;
-            if (col < d) {
+            // d is a multiple of 32, so the 8 lanes of a block are either all inside the row or all outside
+            bf16x4 o4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    hb[i] = (unsigned)__builtin_bit_cast(unsigned short, f2bf(r_keep[i]));
-                    mag = max(mag, hb[i] & 0x7FFFu);
-                }
-            }
-            mag = max(mag, (unsigned)__shfl_xor((int)mag, 1, 64));
-            mag = max(mag, (unsigned)__shfl_xor((int)mag, 2, 64));
-            mag = max(mag, (unsigned)__shfl_xor((int)mag, 4, 64));
-            const int scode = mx_scale_code(mag);
-            if (col < d) {
-                unsigned q4 = 0u;
+            for (int i = 0; i < 4; ++i) o4[i] = f2bf(r_keep[i]);
+            if (c * 256 < d) mx_store_row4(o4, col < d, lane, dstq, dsts, col);
+        } else if (oq != nullptr && c * 256 < d) {
+            bf16x4 o4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) q4 |= mx_encode_bf16(hb[i], scode) << (8 * i);
-                *(unsigned *)(dstq + col) = q4;
-                if ((lane & 7) == 0) dsts[col >> 5] = (unsigned char)scode;
-            }
+            for (int i = 0; i < 4; ++i) o4[i] = f2bf(r_keep[i]);
+            mx_store_row4(o4, col < d, lane, oq + (size_t)row * d, os + (size_t)row * (d >> 5), col);
         }
     }
 }
@@ -214,9 +236,10 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const bf16 *__restrict__ du
 
 int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, const bf16 *gamma,
                   const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d, hipStream_t st,
-                  const EmbedSrc *embed)
+                  const EmbedSrc *embed, unsigned char *u_codes, unsigned char *u_scales)
 {
     if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
+    if (u_codes && (!u_scales || (d % 32))) return -1;
     if (gather && gather->mx && (d % 32)) return -1;
     dim3 grid((T + 3) / 4), block(256);
     ClientTable none;
@@ -226,16 +249,16 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, 
     if (embed) {
         if (!embed->tokens || !embed->wte || !embed->wpe || embed->seq_len <= 0 || embed->vocab <= 0) return -1;
         hipLaunchKernelGGL((ln_fwd_kernel<2>), grid, block, 0, st, nullptr, none, *embed, h_copy, gamma, beta, eps, u,
-                           stats, T, d);
+                           stats, T, d, u_codes, u_scales);
     } else if (gather && gather->mx) {
         hipLaunchKernelGGL((ln_fwd_kernel<3>), grid, block, 0, st, nullptr, *gather, noemb, h_copy, gamma, beta, eps,
-                           u, stats, T, d);
+                           u, stats, T, d, u_codes, u_scales);
     } else if (gather) {
         hipLaunchKernelGGL((ln_fwd_kernel<1>), grid, block, 0, st, nullptr, *gather, noemb, h_copy, gamma, beta, eps,
-                           u, stats, T, d);
+                           u, stats, T, d, u_codes, u_scales);
     } else {
         hipLaunchKernelGGL((ln_fwd_kernel<0>), grid, block, 0, st, h_f32, none, noemb, nullptr, gamma, beta, eps, u,
-                           stats, T, d);
+                           stats, T, d, u_codes, u_scales);
     }
     SL_CHECK_LAUNCH("ln_fwd");
     return 0;
@@ -243,9 +266,10 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, 
 
 int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16 *gamma, const float *dres_f32,
                   const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16, const ClientTable *scatter, int T, int d,
-                  hipStream_t st)
+                  hipStream_t st, unsigned char *o_codes, unsigned char *o_scales)
 {
     if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
+    if (o_codes && (!o_scales || (d % 32) || scatter)) return -1;
     dim3 grid((T + 3) / 4), block(256);
     ClientTable tab;
     tab.K = 0;
@@ -255,21 +279,21 @@ int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16
         // compressed activation gradients: only the first server block scatters, and its residual gradient is fp32
         if ((d % 32) || dres_bf16) return -1;
         hipLaunchKernelGGL((ln_bwd_kernel<false, 2>), grid, block, 0, st, du, h, stats, gamma, (const void *)dres_f32,
-                           out_f32, out_bf16, tab, T, d);
+                           out_f32, out_bf16, tab, T, d, o_codes, o_scales);
     } else if (dres_bf16) {
         if (scatter)
             hipLaunchKernelGGL((ln_bwd_kernel<true, 1>), grid, block, 0, st, du, h, stats, gamma,
-                               (const void *)dres_bf16, out_f32, out_bf16, tab, T, d);
+                               (const void *)dres_bf16, out_f32, out_bf16, tab, T, d, o_codes, o_scales);
         else
             hipLaunchKernelGGL((ln_bwd_kernel<true, 0>), grid, block, 0, st, du, h, stats, gamma,
-                               (const void *)dres_bf16, out_f32, out_bf16, tab, T, d);
+                               (const void *)dres_bf16, out_f32, out_bf16, tab, T, d, o_codes, o_scales);
     } else {
         if (scatter)
             hipLaunchKernelGGL((ln_bwd_kernel<false, 1>), grid, block, 0, st, du, h, stats, gamma,
-                               (const void *)dres_f32, out_f32, out_bf16, tab, T, d);
+                               (const void *)dres_f32, out_f32, out_bf16, tab, T, d, o_codes, o_scales);
         else
             hipLaunchKernelGGL((ln_bwd_kernel<false, 0>), grid, block, 0, st, du, h, stats, gamma,
-                               (const void *)dres_f32, out_f32, out_bf16, tab, T, d);
+                               (const void *)dres_f32, out_f32, out_bf16, tab, T, d, o_codes, o_scales);
     }
     SL_CHECK_LAUNCH("ln_bwd");
     return 0;
