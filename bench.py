@@ -59,10 +59,14 @@ def recorded_gemm_traffic():
     import hashlib
     import re
     path = os.path.join(ROOT, "profiles", "gemm_kernel_workload3_hbm_traffic.md")
-    src = os.path.join(ROOT, "paper_2407_00952_amd", "csrc", "gemm.hip")
+    csrc = os.path.join(ROOT, "paper_2407_00952_amd", "csrc")
     try:
         text = open(path).read()
-        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        # the kernel's source: main loop and launcher, and the epilogue it shares with the fp8 kernel
+        h = hashlib.sha256()
+        for name in ("gemm.hip", "gemm_epilogue.h"):
+            h.update(open(os.path.join(csrc, name), "rb").read())
+        sha = h.hexdigest()
         m_sha = re.search(r"gemm_source_sha256:\s*([0-9a-f]{64})", text)
         m_b = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
         if m_sha and m_b and m_sha.group(1) == sha:

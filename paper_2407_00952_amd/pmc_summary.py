@@ -38,7 +38,10 @@ def main(fetch_csv, write_csv):
         out[name] = dict(cal=sum(cal) / len(cal), factor=factor, n=len(gemm), raw=sum(gemm) / len(gemm),
                          bytes=sum(gemm) / len(gemm) * factor)
     here = os.path.dirname(os.path.abspath(__file__))
-    sha = hashlib.sha256(open(os.path.join(here, "csrc", "gemm.hip"), "rb").read()).hexdigest()
+    h = hashlib.sha256()
+    for name in ("gemm.hip", "gemm_epilogue.h"):          # the GEMM kernel's source (bench.py checks the same digest)
+        h.update(open(os.path.join(here, "csrc", name), "rb").read())
+    sha = h.hexdigest()
     total = out["FETCH_SIZE"]["bytes"] + out["WRITE_SIZE"]["bytes"]
     print("# HBM traffic of the bf16 GEMM kernel, workload 3 (rocprofv3 counters)\n")
     print("Commands (from /tmp with TMPDIR=/tmp, one counter per run):\n")
