@@ -54,8 +54,9 @@ enum { SLORA_LN1_G = 0, SLORA_LN1_B, SLORA_WQKV /* [3d,d]: rows q, then k, then 
 #define SLORA_DTYPE_F32  0
 #define SLORA_DTYPE_BF16 1   /* bf16 storage, fp32 accumulation */
 #define SLORA_DTYPE_MXFP8 2  /* contexts only: as BF16, but every frozen product runs in MXFP8 (Sec. V-B): the
-                                frozen weights are packed once (both orientations), each GEMM's activation
-                                operand is converted right before it, adapters stay in bf16; d_model and
+                                frozen weights are packed once (both orientations), each product's activation
+                                operand is converted by the kernel that produces it or right before the
+                                product, adapters stay in bf16; d_model and
                                 d_ff multiples of 128.  Same calls, same outputs (bf16), looser agreement
                                 with the uncompressed model: a few percent per product */
 
