@@ -329,7 +329,8 @@ def main():
         mx_ms = (time.perf_counter() - t3) / 5 * 1e3
         mx_leg["stack"] = {"ms_per_step": mx_ms, "tokens_per_s": cfg.tokens / (mx_ms * 1e-3),
                            "what": "forward + backward + adapter step of the same workload with the frozen "
-                                   "products in MXFP8 (activations converted before each product)"}
+                                   "products in MXFP8 (activation operands converted by the kernel that produces them or "
+                                   "right before the product)"}
         del srv_mx
         srv = None
 

@@ -209,7 +209,8 @@ def test_workload5_sampled():
     _sampled_parity(synth.CONFIGS[5], [50, 9])
 
 
-def test_round_replays_from_a_hip_graph():
+@pytest.mark.parametrize("dtype", ["bf16", "mxfp8"])
+def test_round_replays_from_a_hip_graph(dtype):
     """Forward + backward + adapter step captured once into a HIP graph and replayed: every replay must
     give bitwise the eager results (the library allocates nothing, synchronises nothing and clears memory
     with kernels only, so its launches can be captured).  Eager work and synchronisations sit between the
@@ -219,7 +220,10 @@ def test_round_replays_from_a_hip_graph():
     inp = _boost_B(synth.make_stack_inputs(cfg), cfg)
 
     def fresh():
-        srv = B.Server(cfg, inp["blocks"], inp["adapters"])
+        # (the compressed type runs the same calls with the frozen products, conversions and rank projections
+        # of its own kernels: they must be capturable too)
+        srv = B.Server(cfg, inp["blocks"], inp["adapters"],
+                       dtype=B.DTYPE_MXFP8 if dtype == "mxfp8" else B.DTYPE_BF16)
         xs = [B.to_device_bf16(c) for c in inp["clients"]]
         y = torch.empty((cfg.n_seq, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
         dy = B.to_device_bf16(inp["dY"])
