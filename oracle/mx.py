@@ -234,11 +234,35 @@ def mx_linear_w4(xq, xs, wq4, ws, bias=None):
 # to the operand as the bf16 tensor it is stored as: Q(bf16(x)) forward, Q(bf16(dy)) and Q(W^T) backward.
 # LayerNorm, attention, GELU and the residual stream are the uncompressed model's.
 
+_W_CACHE = {}
+
+
+def _quantized_weight(W, transposed):
+    """deq(Q(W)) or deq(Q(W^T)), remembered by content: a stack evaluates the same frozen matrices once per
+    sequence, and converting a few million weights in numpy takes longer than the product"""
+    import hashlib
+    W = np.ascontiguousarray(np.asarray(W, dtype=np.float64))
+    key = (W.shape, bool(transposed), hashlib.blake2b(W.tobytes(), digest_size=16).digest())
+    if key not in _W_CACHE:
+        if len(_W_CACHE) > 512:
+            _W_CACHE.clear()
+        M = np.ascontiguousarray(W.T) if transposed else W
+        _W_CACHE[key] = mx_dequantize(*mx_quantize(M))
+    return _W_CACHE[key]
+
+
+def _mx_product(x, W, transposed):
+    """deq(Q(bf16(x))) . deq(Q(W or W^T))^T"""
+    return mx_dequantize(*mx_quantize(bf16_round(x))) @ _quantized_weight(W, transposed).T
+
+
 def _mx_lin_fwd(x, lin, adapters, name, s):
     W, b = lin[name]
     A, B = adapters.get(name, (None, None))
     x = np.asarray(x, dtype=np.float64)
-    y = mx_linear(*mx_quantize(bf16_round(x)), *mx_quantize(W), b)
+    y = _mx_product(x, W, False)
+    if b is not None:
+        y = y + np.asarray(b, dtype=np.float64)[None, :]
     if A is not None:
         y = y + s * ((x @ np.asarray(A, dtype=np.float64).T) @ np.asarray(B, dtype=np.float64).T)
     return y
@@ -248,7 +272,7 @@ def _mx_lin_bwd(x, dy, lin, adapters, name, s, grads):
     W, _ = lin[name]
     A, B = adapters.get(name, (None, None))
     x, dy = np.asarray(x, dtype=np.float64), np.asarray(dy, dtype=np.float64)
-    dx = mx_linear(*mx_quantize(bf16_round(dy)), *mx_quantize(np.ascontiguousarray(np.asarray(W).T)), None)
+    dx = _mx_product(dy, W, True)
     if A is not None:
         A, B = np.asarray(A, dtype=np.float64), np.asarray(B, dtype=np.float64)
         p = dy @ B
