@@ -40,11 +40,23 @@ def _create(**kw):
 @pytest.mark.parametrize("bad", [dict(d_model=100), dict(n_head=3), dict(d_ff=100), dict(n_blocks=0),
                                  dict(lora_r=0), dict(lora_r=17), dict(lora_mask=1 << 6), dict(max_seqs=0),
                                  dict(seq_len=100), dict(dtype=B.DTYPE_F32), dict(ln_eps=0.0),
-                                 dict(d_model=4096, n_head=64)])
+                                 dict(d_model=4096, n_head=64), dict(dtype=3),
+                                 # the compressed type needs widths that are multiples of 128
+                                 dict(dtype=B.DTYPE_MXFP8, d_model=192, n_head=3),
+                                 dict(dtype=B.DTYPE_MXFP8, d_ff=320)])
 def test_create_rejects(bad):
     with pytest.raises(B.SloraError) as e:
         _create(**bad)
     assert e.value.code == B.SLORA_EINVAL
+
+
+def test_compressed_context_needs_room_for_the_packed_weights():
+    plain, comp = _create(), _create(dtype=B.DTYPE_MXFP8)
+    d, dff, L, T = 128, 256, 2, 4 * 128
+    packed = L * 2 * (3 * d * d + d * d + 2 * d * dff)           # 8 operands per block, one byte per weight
+    extra = B.slora_workspace_bytes(comp) - B.slora_workspace_bytes(plain)
+    assert packed <= extra <= packed * 1.2 + T * (max(dff, 3 * d) + d + dff) * 1.1 + 64 * 256
+    B.slora_destroy(plain); B.slora_destroy(comp)
 
 
 def test_workspace_and_binding_errors():
