@@ -233,13 +233,16 @@ def test_lora_linear_mxfp8(T, n_in, n_out, r, with_bias):
     assert relerr(y0, yo) > 4 * BF16_TOL
 
 
-def test_server_round_with_compressed_cut_traffic():
+@pytest.mark.parametrize("ctx_type,d_model,n_head,d_ff", [("bf16", 320, 5, 704), ("mxfp8", 384, 6, 640)])
+def test_server_round_with_compressed_cut_traffic(ctx_type, d_model, n_head, d_ff):
     """slora_server_fwd_mx / slora_server_bwd_mx: the clients' activations arrive as MXFP8 and their gradients
-    leave as MXFP8 (Sec. III-B a2, a4 with the compression of Sec. V-B)."""
+    leave as MXFP8 (Sec. III-B a2, a4 with the compression of Sec. V-B), on a bf16 context and on a context whose
+    frozen products are compressed as well."""
     import torch
     from gpu_util import oracle_of
-    cfg = synth.tiny_config(d_model=320, n_head=5, d_ff=704, n_blocks=2, lora_r=4, lora_proj=("q", "v"),
+    cfg = synth.tiny_config(d_model=d_model, n_head=n_head, d_ff=d_ff, n_blocks=2, lora_r=4, lora_proj=("q", "v"),
                             n_clients=3, batch=2, seq_len=128, seed=synth.BASE_SEED + 77)
+    compressed_ctx = ctx_type == "mxfp8"
     inp = synth.make_stack_inputs(cfg)
     say("compressed cut traffic", cfg.d_model, cfg.n_blocks)
     # ragged client batches: 1, 2 and 3 sequences
@@ -250,7 +253,8 @@ def test_server_round_with_compressed_cut_traffic():
     # what the clients send: the oracle's compression of their activations
     sent = [mx.cut_compress(c) for c in clients]
     received = [mx.mx_dequantize(q, s).astype(np.float32) for q, s in sent]
-    srv = B.Server(cfg, inp["blocks"], inp["adapters"], max_seqs=n_seq)
+    srv = B.Server(cfg, inp["blocks"], inp["adapters"], max_seqs=n_seq,
+                   dtype=B.DTYPE_MXFP8 if compressed_ctx else B.DTYPE_BF16)
     t8 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     xq = [t8(q) for q, _ in sent]; xs = [t8(s) for _, s in sent]
     y = torch.empty((n_seq, S, d), dtype=torch.bfloat16, device="cuda")
@@ -273,7 +277,9 @@ def test_server_round_with_compressed_cut_traffic():
         np.testing.assert_array_equal(dxq[i].cpu().numpy(), q)
         np.testing.assert_array_equal(dxs[i].cpu().numpy(), s)
     # (2) against the oracle: forward on what was received, backward, compression of the gradients
-    orc = oracle_of(cfg, inp)
+    orc = (mx.make_mx_server_oracle(inp["blocks"], inp["adapters"], cfg.n_head, cfg.lora_alpha, cfg.lora_r, cfg.ln_eps)
+           if compressed_ctx else oracle_of(cfg, inp))
+    tol = MX_STACK_TOL if compressed_ctx else BF16_TOL
     Yo = orc.fwd([r.astype(np.float64) for r in received])
     dXo = orc.bwd(dY)
     e = {"Y": relerr(Y, Yo)}
@@ -295,9 +301,9 @@ def test_server_round_with_compressed_cut_traffic():
         if k.startswith("codes"):
             assert v < 0.2, (k, v)
         elif k.startswith("dx"):
-            assert v <= BF16_TOL + 2.0 ** -4, (k, v)
+            assert v <= tol + 2.0 ** -4, (k, v)
         else:
-            assert v <= BF16_TOL, (k, v)
+            assert v <= tol, (k, v)
 
 
 @pytest.mark.parametrize("M,K,ldx", [(64, 128, None), (257, 320, 328), (333, 1024, None)])
