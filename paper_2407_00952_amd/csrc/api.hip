@@ -472,7 +472,8 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
         const BlockWs &b = c->bw[l];
         const auto &fz = c->frozen[l];
         float *h_in = at<float>(c, b.h_in);
-        bf16 *u = at<bf16>(c, b.u ? b.u : c->t_u);
+        // the compressed context reads u, u2 and g as codes; their bf16 copies exist only where an adapter reads them
+        bf16 *u = (c->mx && !b.u) ? nullptr : at<bf16>(c, b.u ? b.u : c->t_u);
         // LN1 (block 0 gathers the clients' activations: S = [s_1; ...; s_N], or looks the embedding up)
         if ((rc = launch_ln_fwd(l == 0 ? nullptr : h_in, l == 0 ? tabp : nullptr, h_in, fz[SLORA_LN1_G],
                                 fz[SLORA_LN1_B], c->cfg.ln_eps, u, at<float>(c, b.stats1), T, d, st,
@@ -508,12 +509,12 @@ static int stack_fwd(slora_ctx *c, const ClientTable *tabp, const EmbedSrc *emb,
             set_mx(c, l, MXW_O, a, mxo);
             if ((rc = launch_gemm(a, EPI_RESID, ad ? 16 : 0, st))) return rc;
         }
-        bf16 *u2 = at<bf16>(c, b.u2 ? b.u2 : c->t_u2);
+        bf16 *u2 = (c->mx && !b.u2) ? nullptr : at<bf16>(c, b.u2 ? b.u2 : c->t_u2);
         if ((rc = launch_ln_fwd(at<float>(c, b.h_mid), nullptr, nullptr, fz[SLORA_LN2_G], fz[SLORA_LN2_B],
                                 c->cfg.ln_eps, u2, at<float>(c, b.stats2), T, d, st, nullptr, qa(c), qas(c))))
             return rc;
         // f = u2 Wfc^T + bfc (+ adapter); g = GELU(f); the slot `f` keeps GELU'(f), all the backward needs
-        bf16 *g = at<bf16>(c, b.g ? b.g : c->t_g);
+        bf16 *g = (c->mx && !b.g) ? nullptr : at<bf16>(c, b.g ? b.g : c->t_g);
         {
             GemmArgs a = gemm_base(u2, d, fz[SLORA_WFC], T, dff, d, fz[SLORA_BFC], c->s);
             a.out0 = at<bf16>(c, b.f); a.out1 = g;
@@ -621,7 +622,10 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
     for (int l = c->L - 1; l >= 0; --l) {
         const BlockWs &b = c->bw[l];
         const auto &fz = c->frozen[l];
-        bf16 *df = at<bf16>(c, c->t_df), *ps = at<bf16>(c, c->t_ps);
+        // compressed mode: df, dh' and the gradient handed down travel as codes; the bf16 copies are written
+        // only where an adapter's products read them
+        bf16 *df = (c->mx && !adapted(c, SLORA_PROJ_FC)) ? nullptr : at<bf16>(c, c->t_df);
+        bf16 *ps = at<bf16>(c, c->t_ps);
         // dg = dh'' Wpr (+ adapter);  df = dg * GELU'(f)
         {
             GemmArgs a = gemm_base(dh2_16, d, at<bf16>(c, b.WprT), T, dff, d, nullptr, c->s);
@@ -655,7 +659,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
         }
         // dh' = dh'' + LN2^T(du2)
         float *dh1_32 = at<float>(c, c->t_dh32[1]);
-        bf16 *dh1_16 = at<bf16>(c, c->t_dh16[1]);
+        bf16 *dh1_16 = (c->mx && !adapted(c, SLORA_PROJ_O)) ? nullptr : at<bf16>(c, c->t_dh16[1]);
         if ((rc = launch_ln_bwd(du2, at<float>(c, b.h_mid), at<float>(c, b.stats2), fz[SLORA_LN2_G], dh2_32,
                                 dh2_32 ? nullptr : dh2_16, dh1_32, dh1_16, nullptr, T, d, st, qa(c), qas(c))))
             return rc;
@@ -717,7 +721,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
         }
         // dh = dh' + LN1^T(du): next block's incoming gradient, or the clients' activation gradients
         float *nx32 = at<float>(c, c->t_dh32[0]);
-        bf16 *nx16 = at<bf16>(c, c->t_dh16[0]);
+        bf16 *nx16 = (c->mx && !adapted(c, SLORA_PROJ_PR)) ? nullptr : at<bf16>(c, c->t_dh16[0]);
         if (l > 0) {
             if ((rc = launch_ln_bwd(dub, at<float>(c, b.h_in), at<float>(c, b.stats1), fz[SLORA_LN1_G], dh1_32,
                                     nullptr, nx32, nx16, nullptr, T, d, st, qa(c), qas(c))))

@@ -88,17 +88,23 @@ __device__ __forceinline__ void store_row8(const Args &a, int row, int col, floa
             wg[i] = f2bf(gv);
         }
         *(bf16x8 *)((bf16 *)a.out0 + o) = wf;
-        *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
         if constexpr (Args::kEmitCodes) {
+            // compressed mode: the bf16 copy of g is only written when somebody reads it (an adapter on the
+            // next projection); the product that consumes g takes the codes
+            if (a.out1) *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
             if (a.oq) store_codes8(a, row, col, wg);
+        } else {
+            *(bf16x8 *)((bf16 *)a.out1 + o) = wg;
         }
     } else {   // EPI_DGELU
         bf16x8 w;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i] * bf2f(x.f[i]));   // aux holds GELU'(f)
-        *(bf16x8 *)((bf16 *)a.out0 + o) = w;
         if constexpr (Args::kEmitCodes) {
+            if (a.out0) *(bf16x8 *)((bf16 *)a.out0 + o) = w;
             if (a.oq) store_codes8(a, row, col, w);
+        } else {
+            *(bf16x8 *)((bf16 *)a.out0 + o) = w;
         }
     }
 }

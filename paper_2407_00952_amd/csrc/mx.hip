@@ -565,6 +565,7 @@ int launch_gemm_mx_stack(const GemmArgs &g, int epi, int nz, hipStream_t st)
     if ((g.K % 128) || (g.seg_n % 8) || g.ldw != g.K || !m.wq || !m.ws || !m.xq || !m.xs) return -1;
     if ((unsigned long long)g.M * g.K >= (1ull << 32) || (unsigned long long)g.N * g.K >= (1ull << 32)) return -1;
     int rc;
+    if (!m.x_ready && !g.X) return -1;
     if (!m.x_ready && (rc = launch_quantize(g.X, g.ldx, g.M, g.K, m.xq, m.xs, st))) return rc;
     MxArgs a = mx_plain(m.xq, m.xs, m.wq, m.ws, g.bias, g.out0, g.M, g.N, g.K);
     a.nseg = g.nseg; a.seg_n = g.seg_n;
@@ -573,12 +574,15 @@ int launch_gemm_mx_stack(const GemmArgs &g, int epi, int nz, hipStream_t st)
         if (!g.os || (g.ldo % 32) || (g.seg_n % 32) || (epi != EPI_GELU && epi != EPI_DGELU)) return -1;
         a.oq = g.oq; a.os = g.os;
     }
+    // the bf16 copy of the tensor that also goes out as codes may be left out; everything else must exist
+    if (!(epi == EPI_GELU ? g.out0 && (g.out1 || g.oq) : epi == EPI_DGELU ? (g.out0 || g.oq) : g.out0 || g.out1))
+        return -1;
     if (nz > 0) {
         a.K2 = g.K2; a.ldt = g.ldt;
         for (int sgm = 0; sgm < g.nseg; ++sgm) {
             if (!g.zmat[sgm]) continue;
             // the bf16 kernel forms these inside its K loop from the bf16 tile; here the tile is fp8
-            if (!g.zspill[sgm] || !g.tmat[sgm]) return -1;
+            if (!g.zspill[sgm] || !g.tmat[sgm] || !g.X) return -1;
             if ((rc = launch_rank_project(g.X, g.ldx, g.M, g.K, g.zmat[sgm], g.ldz, nz, g.zscale, g.zspill[sgm], st)))
                 return rc;
             a.zs[sgm] = g.zspill[sgm];

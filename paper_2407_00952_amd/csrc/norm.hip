@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ h
             bf16x4 bt = *(const bf16x4 *)(beta + col);
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = f2bf(v[c][i] * rho * bf2f(gm[i]) + bf2f(bt[i]));
-            *(bf16x4 *)(u + (size_t)row * d + col) = o;
+            if (u != nullptr) *(bf16x4 *)(u + (size_t)row * d + col) = o;    // (null: only the codes are wanted)
         }
         if (uq != nullptr && c * 256 < d)
             mx_store_row4(o, col < d, lane, uq + (size_t)row * d, us + (size_t)row * (d >> 5), col);
@@ -240,6 +240,7 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, 
 {
     if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
     if (u_codes && (!u_scales || (d % 32))) return -1;
+    if (!u && !u_codes) return -1;
     if (gather && gather->mx && (d % 32)) return -1;
     dim3 grid((T + 3) / 4), block(256);
     ClientTable none;
