@@ -435,6 +435,9 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         __syncthreads();
         G4_STEPC(1, 0, xnxt, wnxt, 0, min((kt + 2) * BK, klast), min((kt + 3) * BK, klast))
         xcur = xnxt; wcur = wnxt;
+        // after the last slab, still inside the loop body: the last MFMAs retire before anything the
+        // compiler places behind the loop can read an accumulator (it takes them for finished)
+        if (kt + 1 >= nk) asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
     }
 #undef G4_COPYX
 #undef G4_COPYW
