@@ -118,3 +118,29 @@ def test_bf16_zero_B_is_bitwise_base():
     y_lora, dx_lora = _run_bf16(c0)[:2]
     y_base, dx_base = _run_bf16(c1)[:2]
     assert np.array_equal(y_lora, y_base) and np.array_equal(dx_lora, dx_base)
+
+
+# The frozen product on its own (Sec. II-C without the adapter): this is the launch shape of the stack's
+# products that have no rank-space branch, i.e. the 4-wave GEMM kernel with the plain-store epilogue.  One
+# k-slab, an odd number of slabs, ragged row and column tiles, a single row, with and without bias.
+@pytest.mark.parametrize("T,n_in,n_out,bias", [
+    (700, 320, 448, True),
+    (1, 64, 8, True),
+    (257, 64, 264, False),
+    (300, 704, 320, True),
+    (1300, 1024, 3072, False),
+    (4096, 4096, 1024, True),
+])
+def test_frozen_linear_bf16(T, n_in, n_out, bias):
+    import torch
+    c = synth.make_single_layer(T, n_in, n_out, 1, seed=300 + T + n_in, quant=True, bias=bias)
+    x, W = B.to_device_bf16(c["x"]), B.to_device_bf16(c["W"])
+    b = None if c["b"] is None else B.to_device_bf16(c["b"])
+    y = torch.empty((T, n_out), dtype=torch.bfloat16, device="cuda")
+    B.slora_frozen_linear_bf16(T, n_in, n_out, x, W, b, y)
+    torch.cuda.synchronize()
+    ref, _ = so.lora_linear_fwd(c["x"], c["W"], c["b"], np.zeros_like(c["A"]), np.zeros_like(c["B"]), 1.0)
+    e = relerr(B.from_device_bf16(y), ref)
+    say("frozen linear", T, n_in, n_out, "rel err %.2e" % e)
+    # fp32 accumulation and one rounding to bf16: half a bf16 ulp of the largest output
+    assert e <= 2.0 ** -8
