@@ -82,11 +82,19 @@ __device__ __forceinline__ bf16x8 frag_tr(const unsigned char *t, int col0, int 
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
                                                        bf16 *__restrict__ o_lo, float *__restrict__ lse, int S,
-                                                       int H)
+                                                       int H, int n_seq)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
-    const int qt = gridDim.x - 1 - blockIdx.x;          // longest rows first
-    const int a = blockIdx.y, n = blockIdx.z;
+    // Block -> (query tile, head, sequence).  Workgroups are handed to the 8 XCDs round-robin, so the
+    // blocks of one (sequence, head) - which read the same K and V tiles - are given ids that land on ONE
+    // XCD, next to each other in dispatch order: its L2 then serves the re-reads (with the tiles of a head
+    // spread over four XCDs the kernel fetched twice its algorithmic bytes from memory).
+    const int nqt = (S + 127) >> 7;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int pair = (idx / nqt) * 8 + xcd;             // (sequence, head) pair
+    if (pair >= H * n_seq) return;
+    const int qt = nqt - 1 - idx % nqt;                 // longest rows first
+    const int a = pair % H, n = pair / H;
     const int d = H * 64, ld = 3 * d;
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -660,8 +668,10 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
 int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st)
 {
     if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return -1;
-    dim3 grid((S + 127) / 128, H, n_seq);
-    hipLaunchKernelGGL(attn_fwd_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, lse, S, H);
+    const long long pairs8 = ((long long)H * n_seq + 7) / 8 * 8;
+    const long long nblk = pairs8 * ((S + 127) / 128);
+    if (nblk > 0x7fffffffLL) return -1;
+    hipLaunchKernelGGL(attn_fwd_kernel, dim3((unsigned)nblk), dim3(256), 0, st, qkv, o, o_lo, lse, S, H, n_seq);
     SL_CHECK_LAUNCH("attn_fwd");
     return 0;
 }
