@@ -125,13 +125,19 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
     const int kv_end = min(S, qt * 128 + 128);
     const int ntile = kv_end >> 6;
 
+    // All 8 K fragments and all 16 V fragment reads of a tile are issued before the first MFMA, so the LDS
+    // latency is paid once per tile instead of once per fragment (left inline in the MFMA calls the compiler
+    // emitted read, wait, MFMA for every one of them), and the two score accumulators advance alternately.
 #define FWD_TILE(Ks, Vs, k0)                                                                           \
     if (active && (k0) <= qb + 31) {                                                                   \
+        bf16x8 kf[2][4];                                                                               \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                               \
+            _Pragma("unroll") for (int mt = 0; mt < 2; ++mt) kf[mt][ks] = frag_rm(Ks, mt * 32 + r32, ks, g); \
+        __builtin_amdgcn_sched_barrier(0);                                                             \
         f32x16 sacc[2] = {zero16(), zero16()};                                                         \
-        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                           \
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm(Ks, mt * 32 + r32, ks, g),  \
-                                                                    qf[ks], sacc[mt], 0, 0, 0);        \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                               \
+            _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                           \
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][ks], qf[ks], sacc[mt], 0, 0, 0); \
         if ((k0) + 63 > qb) {                                                                          \
             _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                           \
                 _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                       \
@@ -151,16 +157,23 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
             _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                           \
                 _Pragma("unroll") for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;                   \
         }                                                                                              \
-        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt)                                               \
+        _Pragma("unroll") for (int mt = 0; mt < 2; ++mt) {                                             \
+            bf16x8 vf[2][2];                             /* this half's V fragments, under way during its exponentials */ \
+            _Pragma("unroll") for (int hh = 0; hh < 2; ++hh)                                           \
+                _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
+                    vf[hh][dt] = frag_tr(Vs, 32 * dt, 32 * mt + 16 * hh, lane);                        \
+            __builtin_amdgcn_sched_barrier(0);                                                         \
             _Pragma("unroll") for (int hh = 0; hh < 2; ++hh) {                                         \
                 bf16x8 pb;                                                                             \
-                _Pragma("unroll") for (int i = 0; i < 8; ++i)                                          \
-                    pb[i] = f2bf(__builtin_amdgcn_exp2f(fmaf(sacc[mt][8 * hh + i], kScaleLog2, -m)));  \
+                float pe[8];                                                                           \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) pe[i] = fmaf(sacc[mt][8 * hh + i], kScaleLog2, -m); \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) pe[i] = __builtin_amdgcn_exp2f(pe[i]);   \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) pb[i] = f2bf(pe[i]);                     \
                 lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, lacc, 0, 0, 0);               \
                 _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                \
-                        frag_tr(Vs, 32 * dt, 32 * mt + 16 * hh, lane), pb, oacc[dt], 0, 0, 0);         \
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hh][dt], pb, oacc[dt], 0, 0, 0); \
             }                                                                                          \
+        }                                                                                              \
     }
 
     const bf16 *kg = base + d, *vg = base + 2 * d;
