@@ -227,11 +227,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
                                                           const bf16 *__restrict__ o_lo,
                                                           const bf16 *__restrict__ dout,
                                                           const float *__restrict__ lse, float *__restrict__ delta,
-                                                          bf16 *__restrict__ dqkv, int S, int H)
+                                                          bf16 *__restrict__ dqkv, int S, int H, int n_seq)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
-    const int qt = gridDim.x - 1 - blockIdx.x;
-    const int a = blockIdx.y, n = blockIdx.z;
+    // block ids decoded as in the forward: the query tiles of a (sequence, head) share an XCD
+    const int nqt = (S + 127) >> 7;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int pair = (idx / nqt) * 8 + xcd;
+    if (pair >= H * n_seq) return;
+    const int qt = nqt - 1 - idx % nqt;
+    const int a = pair % H, n = pair / H;
     const int d = H * 64, ld = 3 * d;
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -335,12 +340,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
                                                            const bf16 *__restrict__ dout,
                                                            const float *__restrict__ lse,
                                                            const float *__restrict__ delta,
-                                                           bf16 *__restrict__ dqkv, int S, int H)
+                                                           bf16 *__restrict__ dqkv, int S, int H, int n_seq)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char Q0[TILE_B], D0[TILE_B], Q1[TILE_B], D1[TILE_B];
     __shared__ __align__(16) float st0[128], st1[128];   // lse | delta of the 64 queries of a tile
-    const int kvt = blockIdx.x;                          // keys kvt*128 ..: most work first
-    const int a = blockIdx.y, n = blockIdx.z;
+    // block ids decoded as in the forward: the key tiles of a (sequence, head) share an XCD
+    const int nkt = (S + 127) >> 7;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int pair = (idx / nkt) * 8 + xcd;
+    if (pair >= H * n_seq) return;
+    const int kvt = idx % nkt;                           // keys kvt*128 ..: most work first
+    const int a = pair % H, n = pair / H;
     const int d = H * 64, ld = 3 * d;
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -698,10 +708,13 @@ int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16
         SL_CHECK_LAUNCH("attn_bwd_fused");
         return 0;
     }
-    dim3 grid((S + 127) / 128, H, n_seq);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, dout, lse, delta, dqkv, S, H);
+    const long long pairs8 = ((long long)H * n_seq + 7) / 8 * 8;
+    const long long nblk = pairs8 * ((S + 127) / 128);
+    if (nblk > 0x7fffffffLL) return -1;
+    const dim3 grid((unsigned)nblk);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, dout, lse, delta, dqkv, S, H, n_seq);
     SL_CHECK_LAUNCH("attn_bwd_dq");
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, dim3(256), 0, st, qkv, dout, lse, delta, dqkv, S, H);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, dim3(256), 0, st, qkv, dout, lse, delta, dqkv, S, H, n_seq);
     SL_CHECK_LAUNCH("attn_bwd_dkv");
     return 0;
 }
