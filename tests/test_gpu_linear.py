@@ -99,6 +99,10 @@ def test_fp32_zero_B_is_bitwise_base():
     (64, 128, 128, 1, False),
     (512, 768, 768, 2, True),        # the remaining ranks of the paper's sweep r in {1, 2, 4, 8} (Sec. IV)
     (512, 768, 2304, 8, False),
+    # 34 chunks of 512 tokens, the last one ragged: each wavefront of the adapter-gradient reduction sums
+    # nine chunks (the body with eight loads in flight plus its tail), the last wavefront seven (tail only)
+    (16960, 256, 64, 4, True),
+    (16960, 64, 256, 16, False),
 ])
 def test_bf16_layer(T, n_in, n_out, r, bias):
     c = synth.make_single_layer(T, n_in, n_out, r, seed=100 + T + r, quant=True, bias=bias)
