@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 
 
 def model_flops_per_token(cfg):
@@ -51,6 +52,123 @@ def cpu_baseline(cfg, inp, budget_s=20.0):
     return {"value": n * cfg.seq_len / el, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": "%d whole sequence(s) of %d tokens, forward+backward through all %d blocks, numpy fp64"
                       % (n, cfg.seq_len, cfg.n_blocks)}
+
+
+def kernel_rooflines(step_fn, n_steps=3):
+    """Per-kernel rates of the step's other kernels from HIP events around every launch (a separate pass after
+    the timed region: bracketing ~370 launches per step with events would slow the timed step itself).
+    HBM-bound kinds: algorithmic bytes / time against the HBM peak; attention: algorithmic flop / time against
+    the bf16 MFMA peak."""
+    import torch
+    from paper_2407_00952_amd import binding as B
+    kinds = {"ln_fwd_kernel": (B.PROF_LN_FWD, "hbm"), "ln_bwd_kernel": (B.PROF_LN_BWD, "hbm"),
+             "lora_grad_partial_kernel": (B.PROF_LORA_GRAD, "hbm"), "sgd_table_kernel": (B.PROF_SGD, "hbm"),
+             "attn_fwd_kernel": (B.PROF_ATTN_FWD, "mfma"), "attn_bwd_kernel(s)": (B.PROF_ATTN_BWD, "mfma")}
+    mask = 0
+    for k, _ in kinds.values():
+        mask |= 1 << k
+    B.slora_prof_enable(mask)
+    for _ in range(n_steps):
+        step_fn()
+    torch.cuda.synchronize()
+    hbm, mfma = {}, {}
+    for name, (k, bound) in kinds.items():
+        ms, work, n = B.slora_prof_read_kind(k)
+        if n == 0 or ms <= 0:
+            continue
+        if bound == "hbm":
+            gbs = work / (ms * 1e-3) / 1e9
+            hbm[name] = {"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                         "bytes_per_launch": work / n, "avg_launch_us": ms / n * 1e3, "launches_per_step": n // n_steps}
+        else:
+            tf = work / (ms * 1e-3) / 1e12
+            mfma[name] = {"achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS,
+                          "flop_per_launch": work / n, "avg_launch_us": ms / n * 1e3, "launches_per_step": n // n_steps}
+    B.slora_prof_enable(0)
+    return hbm, mfma
+
+
+def fedavg_hbm_rate(stream, n_sets=4, reps=10):
+    """Eq. (8)-(9) at workload 5's size (16 client adapter sets of 6 blocks, r = 16, all six projections:
+    16 x 1 769 472 floats in, one set out = 120.3 MB per call) over `n_sets` DISTINCT buffer sets used in
+    rotation, 481 MB in all, which no cache level holds: an HBM rate.  The same call repeated on one set
+    (whose 120 MB stay in the last-level cache) is reported beside it."""
+    import torch
+    from paper_2407_00952_amd import binding as B
+    from paper_2407_00952_amd import synth
+    cfg5 = synth.CONFIGS[5]
+    n, K = synth.fedavg_param_count(cfg5), cfg5.n_clients
+    rng = np.random.Generator(np.random.PCG64(cfg5.seed + 1000))
+    counts = rng.integers(100, 1001, size=K).astype(np.int64)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(cfg5.seed + 1001)
+    sets = [[torch.randn(n, device="cuda", generator=g) * 0.02 for _ in range(K)] for _ in range(n_sets)]
+    outs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(n_sets)]
+    nbytes = 4.0 * (K + 1) * n
+
+    def run(rotate):
+        for i in range(n_sets):
+            B.slora_fedavg(sets[i], counts, n, outs[i], stream)
+        torch.cuda.synchronize()
+        B.slora_prof_enable(1 << B.PROF_FEDAVG)
+        for rep in range(reps):
+            for i in range(n_sets):
+                j = i if rotate else 0
+                B.slora_fedavg(sets[j], counts, n, outs[j], stream)
+        torch.cuda.synchronize()
+        ms, work, cnt = B.slora_prof_read_kind(B.PROF_FEDAVG)
+        B.slora_prof_enable(0)
+        return work / (ms * 1e-3) / 1e9, ms / cnt * 1e3
+
+    gbs, us = run(True)
+    gbs_same, us_same = run(False)
+    return {"kernel": "fedavg_kernel", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+            "bytes_per_launch": nbytes, "avg_launch_us": us, "clients": K, "params": n,
+            "buffer_sets_rotated": n_sets, "working_set_bytes": nbytes * n_sets,
+            "same_buffers_gb_s": gbs_same, "same_buffers_us": us_same,
+            "what": "workload 5's aggregation; rotated over distinct buffer sets so that no cache holds them"}
+
+
+def other_workload(w, lr, steps=5, warmup=2):
+    """tokens/s and GEMM rate of another workload's step (forward + backward + adapter step), same protocol."""
+    import torch
+    from paper_2407_00952_amd import binding as B
+    from paper_2407_00952_amd import synth
+    cfg = synth.CONFIGS[w]
+    inp = synth.make_stack_inputs(cfg)
+    srv = B.Server(cfg, inp["blocks"], inp["adapters"])
+    xs = [B.to_device_bf16(c) for c in inp["clients"]]
+    y = torch.empty((cfg.n_seq, cfg.seq_len, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    dy = B.to_device_bf16(inp["dY"])
+    dxs = [torch.empty_like(x) for x in xs]
+    del inp
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        srv.fwd(xs, y, stream)
+        srv.bwd(dy, dxs, stream)
+        srv.step(lr, stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    B.slora_prof_enable(1 << B.PROF_GEMM)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    el = (time.perf_counter() - t0) / steps
+    gemm_ms, gemm_flop, launches = B.slora_prof_read()
+    B.slora_prof_enable(0)
+    srv.close()
+    ach = gemm_flop / (gemm_ms * 1e-3) / 1e12
+    fg, fa, fl = model_flops_per_token(cfg)
+    return {"workload": "%s: %d blocks, d=%d, d_ff=%d, r=%d on %s, %d x %d x %d tokens" % (
+                cfg.name, cfg.n_blocks, cfg.d_model, cfg.d_ff, cfg.lora_r, ",".join(cfg.lora_proj), cfg.n_clients,
+                cfg.batch, cfg.seq_len),
+            "tokens_per_step": cfg.tokens, "ms_per_step": el * 1e3, "tokens_per_s": cfg.tokens / el,
+            "model_tflops": (fg + fa + fl) * cfg.tokens / el / 1e12,
+            "gemm_tflops": ach, "gemm_frac_of_bf16_peak": ach / PEAK_BF16_TFLOPS, "steps": steps}
 
 
 def recorded_gemm_traffic():
@@ -174,6 +292,8 @@ def main():
                          "the loss head is timed on its own after the timed region")
     ap.add_argument("--no-legs", action="store_true",
                     help="skip the separately timed loss-head and client-side legs (profiles of the metric's step)")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the other workloads (2, 4, 5) that are timed after the metric's own")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps, run a plain copy of known size (FedAvg with one client, "
                          "256 MiB in, 256 MiB out) so that HBM byte counters can be scaled")
@@ -234,7 +354,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.slora_prof_enable(1)
+    B.slora_prof_enable(1 << B.PROF_GEMM)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -242,6 +362,9 @@ def main():
     el = time.perf_counter() - t0
     gemm_ms, gemm_flop, launches = B.slora_prof_read()
     B.slora_prof_enable(0)
+    hbm_kernels = attn_kernels = None
+    if not args.no_legs:
+        hbm_kernels, attn_kernels = kernel_rooflines(step)
 
     # the four calls of the step on their own (after the timed region, outside the GEMM statistics)
     phases = None
@@ -334,6 +457,17 @@ def main():
         del srv_mx
         srv = None
 
+    fed5 = others = None
+    if legs:
+        fed5 = fedavg_hbm_rate(stream)
+    if legs and not args.no_workloads and args.workload == 3:
+        xs = y = dy = dxs = None
+        torch.cuda.empty_cache()
+        others = {}
+        for w in (2, 4, 5):
+            others[str(w)] = other_workload(w, lr)
+            torch.cuda.empty_cache()
+
     if args.copy_calibration:
         n_cal = 64 * 1024 * 1024
         src = torch.ones(n_cal, dtype=torch.float32, device="cuda")
@@ -366,6 +500,13 @@ def main():
                      "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
                      "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
     }
+    if hbm_kernels is not None:
+        if fed5 is not None:
+            hbm_kernels["fedavg_kernel (workload 5)"] = fed5
+        out["hbm_kernels"] = hbm_kernels
+        out["attention_kernels"] = attn_kernels
+    if others is not None:
+        out["workloads"] = others
     if phases is not None:
         out["phases"] = phases
     if legs:

@@ -66,7 +66,7 @@ enum { SLORA_LN1_G = 0, SLORA_LN1_B, SLORA_WQKV /* [3d,d]: rows q, then k, then 
 typedef struct slora_ctx slora_ctx;      /* opaque, host memory */
 
 typedef struct {
-    int32_t  d_model;      /* multiple of 64; head size d_model / n_head must be 64            */
+    int32_t  d_model;      /* multiple of 64, at most 2048; head size d_model / n_head must be 64 */
     int32_t  n_head;
     int32_t  d_ff;         /* multiple of 64                                                   */
     int32_t  n_blocks;     /* server-side blocks only                                          */
@@ -78,6 +78,9 @@ typedef struct {
     int32_t  max_seqs;     /* upper bound on the number of sequences per round (sum of b_i)    */
     int32_t  seq_len;      /* S, multiple of 64, every sequence has exactly this length        */
 } slora_config;
+/* Further limits checked by slora_create (SLORA_EINVAL): n_blocks <= 1024; max_seqs * seq_len <= 2^24 tokens;
+ * max_seqs * seq_len * max(3 * d_model, d_ff) < 2^31 elements (the kernels address a GEMM operand with 32-bit
+ * byte offsets from its base). */
 
 /* ---- context (host only) ---------------------------------------------------------------- */
 int    slora_create(const slora_config *cfg, slora_ctx **out);
@@ -88,8 +91,11 @@ int    slora_destroy(slora_ctx *ctx);
 size_t slora_workspace_bytes(const slora_ctx *ctx);
 /* ws must be 256-byte aligned and stay alive while the context is used. */
 int    slora_bind_workspace(slora_ctx *ctx, void *ws, size_t bytes);
-/* Borrow one frozen tensor (bf16, shapes above) of block `block`; never written.  The next
- * forward call queues the (one-off) transposed copies used by the backward pass. */
+/* Borrow one frozen tensor (bf16, shapes above, 16-byte aligned) of block `block`; never written.  The
+ * first forward call after any bind queues the one-off set-up kernels (transposed copies of the frozen weights
+ * for the backward pass, the descriptor tables of the adapters); like every other call it only queues kernels,
+ * so it neither blocks nor prevents stream capture (a captured first forward repeats the set-up on every
+ * replay: run one round eagerly first if that matters). */
 int    slora_bind_frozen(slora_ctx *ctx, int block, int which, const void *w);
 /* Borrow the fp32 master adapter of projection `proj` in block `block`: A [r,in], B [out,r],
  * and the gradient buffers dA [r,in], dB [out,r].  A, B are changed only by
@@ -133,7 +139,9 @@ int slora_fedavg(int K, const float *const *h_client_params, const int64_t *h_sa
 /* ---- one LoRA-adapted linear layer (Sec. II-C), used on its own -------------------------------- */
 /* y [T,out] = x [T,in] W[out,in]^T + bias + (alpha/r) (x A^T) B^T.  dtype F32: every buffer fp32.
  * dtype BF16: x, W, bias, y bf16 and A, B fp32; `ws` is scratch of slora_lora_linear_ws_bytes().
- * bias may be NULL.  r in 1..SLORA_MAX_RANK; in, out multiples of 64 for BF16. */
+ * bias may be NULL.  r in 1..SLORA_MAX_RANK.  BF16: in, out multiples of 64; x, W, y, dy, dx 16-byte aligned;
+ * T * max(in, out) < 2^31 and in * out < 2^31 elements.  slora_lora_linear_ws_bytes returns 0 for sizes
+ * outside these limits; the calls return SLORA_EINVAL. */
 size_t slora_lora_linear_ws_bytes(int dtype, int T, int n_in, int n_out, int r);
 int slora_lora_linear_fwd(int dtype, int T, int n_in, int n_out, int r, float alpha,
                           const void *x, const void *W, const void *bias, const float *A, const float *B,
@@ -145,8 +153,9 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
                           void *dx, float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
 
 /* The frozen product alone (Sec. II-C with no adapter): y [T,out] = x [T,in] W[out,in]^T + bias, all
- * bf16 with fp32 accumulation; bias may be NULL; in a multiple of 64.  Runs the same GEMM kernel as the
- * stack and needs no scratch. */
+ * bf16 with fp32 accumulation; bias may be NULL.  in a multiple of 64, out a multiple of 8; x, W, y 16-byte
+ * aligned; T * max(in, out) < 2^31 and in * out < 2^31 elements (SLORA_EINVAL otherwise).  Runs the same GEMM
+ * kernel as the stack and needs no scratch. */
 int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias,
                              void *y, void *stream);
 
@@ -275,12 +284,26 @@ int slora_mx_lora_linear_bwd(int32_t T, int32_t n_in, int32_t n_out, int32_t r, 
                              float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- measurement hook (not part of the method) ---------------------------------------------------- */
-/* While enabled, every launch of the bf16 GEMM kernel (the frozen products of Sec. II-C with the
- * fused low-rank branch) is bracketed by HIP events on its stream.  slora_prof_read waits for the
- * recorded events (it BLOCKS the host), returns the summed kernel time in milliseconds, the summed
- * algorithmic work 2*M*N*K in flop and the number of launches recorded (at most 8192 between two
- * reads), and resets the counters.  Process-wide, not thread-safe. */
-int slora_prof_enable(int on);
+/* Kernel launches of the kinds selected by slora_prof_enable (bit k of `kinds` = kind k; 0 = off; 1 = the
+ * bf16 GEMM launches only) are bracketed by HIP events on their stream.  slora_prof_read_kind waits for the
+ * recorded events (it BLOCKS the host) and returns, for one kind, the summed kernel time in milliseconds, the
+ * summed algorithmic work of those launches and their number.  Work is in flop for the matrix-core kinds --
+ * GEMM: 2*M*N*K of the frozen product (Sec. II-C); attention: 2*S*d per token forward, 4*S*d backward, lower
+ * triangle only -- and in bytes for the HBM-bound kinds: each tensor the kernel must read or write, once.
+ * At most 16384 launches are recorded between two calls of slora_prof_enable, which also clears the record.
+ * slora_prof_read is slora_prof_read_kind(SLORA_PROF_GEMM, ...).  Process-wide, not thread-safe.
+ * SLORA_EINVAL for an unknown kind, SLORA_EHIP if an event call fails. */
+enum { SLORA_PROF_GEMM = 0,      /* frozen products with the fused low-rank branch (flop)                 */
+       SLORA_PROF_LN_FWD,        /* LayerNorm forward (bytes)                                              */
+       SLORA_PROF_LN_BWD,        /* LayerNorm backward + residual gradient (bytes)                         */
+       SLORA_PROF_LORA_GRAD,     /* streaming pass of an adapter gradient dA or dB (bytes)                 */
+       SLORA_PROF_SGD,           /* Eq. (4)-(5) over all adapters (bytes)                                  */
+       SLORA_PROF_ATTN_FWD,      /* attention forward (flop)                                               */
+       SLORA_PROF_ATTN_BWD,      /* attention backward (flop)                                              */
+       SLORA_PROF_FEDAVG,        /* Eq. (8)-(9) (bytes)                                                    */
+       SLORA_PROF_KINDS };
+int slora_prof_enable(int kinds);
+int slora_prof_read_kind(int kind, double *h_ms, double *h_work, int *h_launches);
 int slora_prof_read(double *h_gemm_ms, double *h_gemm_flop, int *h_launches);
 
 const char *slora_strerror(int code);

@@ -32,7 +32,9 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_frozen_linear_mxfp8", "slora_mx_weight_bytes", "slora_mx_pack_weight",
            "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd",
            "slora_server_fwd_mx", "slora_server_bwd_mx", "slora_mx_quantize_fp4",
-           "slora_frozen_linear_mxfp8_w4"]
+           "slora_frozen_linear_mxfp8_w4", "slora_prof_read_kind"]
+(PROF_GEMM, PROF_LN_FWD, PROF_LN_BWD, PROF_LORA_GRAD, PROF_SGD, PROF_ATTN_FWD, PROF_ATTN_BWD, PROF_FEDAVG,
+ PROF_KINDS) = range(9)
 
 
 class slora_config(ctypes.Structure):
@@ -100,6 +102,7 @@ def lib():
         L.slora_mx_lora_linear_bwd.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_prof_enable.argtypes = [i32]
         L.slora_prof_read.argtypes = [vp, vp, vp]
+        L.slora_prof_read_kind.argtypes = [i32, vp, vp, vp]
         L.slora_strerror.argtypes = [i32]
         L.slora_strerror.restype = ctypes.c_char_p
         L.slora_last_hip_error.restype = ctypes.c_char_p
@@ -290,15 +293,22 @@ def slora_loss_head(T, d_model, vocab, y, lnf_g, lnf_b, eps, labels, ws, ws_byte
                                  _p(loss_tok), _p(loss), _p(dy), _stream(stream)))
 
 
-def slora_prof_enable(on):
-    _check(lib().slora_prof_enable(int(on)))
+def slora_prof_enable(kinds):
+    _check(lib().slora_prof_enable(int(kinds)))
 
 
 def slora_prof_read():
-    """(gemm_ms, gemm_flop, launches) accumulated since the last read; blocks on the recorded events."""
+    """(gemm_ms, gemm_flop, launches) recorded since slora_prof_enable; blocks on the recorded events."""
     ms, fl, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
     _check(lib().slora_prof_read(ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(n)))
     return ms.value, fl.value, n.value
+
+
+def slora_prof_read_kind(kind):
+    """(ms, work, launches) of one kind of kernel recorded since slora_prof_enable."""
+    ms, wk, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+    _check(lib().slora_prof_read_kind(int(kind), ctypes.byref(ms), ctypes.byref(wk), ctypes.byref(n)))
+    return ms.value, wk.value, n.value
 
 
 # ---- buffer management for tests and the benchmark (allocation + marshalling only) -----------------

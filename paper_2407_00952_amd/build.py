@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libslora.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "lora_misc.hip", "f32_linear.hip", "loss_head.hip", "mx.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "lora_misc.hip", "f32_linear.hip", "loss_head.hip", "mx.hip", "prof.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

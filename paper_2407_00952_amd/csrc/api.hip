@@ -1,9 +1,9 @@
 // C ABI of libslora: context, workspace layout and the per-block kernel schedule of the
 // server-side step of split federated LoRA fine-tuning (SplitLoRA Sec. III-B a3, a4, b2).
-// Host code only; every device operation is a kernel launch (or one async table upload)
-// on the caller's stream.
+// Host code only; every device operation is a kernel launch on the caller's stream.
 #include "../../include/slora.h"
 #include "common.h"
+#include "prof.h"
 
 #include <array>
 #include <cmath>
@@ -18,8 +18,13 @@ int f32_lora_linear_bwd(int T, int n_in, int n_out, int r, float s, const float 
                         const float *W, const float *A, const float *B, float *dx, float *dA, float *dB, float *ws,
                         hipStream_t st);
 
-int gemm_prof_enable(int on);
-int gemm_prof_read(double *ms, double *flop, int *launches);
+static_assert(PK_GEMM == SLORA_PROF_GEMM && PK_LN_FWD == SLORA_PROF_LN_FWD && PK_LN_BWD == SLORA_PROF_LN_BWD &&
+              PK_LORA_GRAD == SLORA_PROF_LORA_GRAD && PK_SGD == SLORA_PROF_SGD && PK_ATTN_FWD == SLORA_PROF_ATTN_FWD &&
+              PK_ATTN_BWD == SLORA_PROF_ATTN_BWD && PK_FEDAVG == SLORA_PROF_FEDAVG && PK_COUNT == SLORA_PROF_KINDS,
+              "kinds of the measurement hook");
+static_assert(SL_OK == SLORA_OK && SL_EINVAL == SLORA_EINVAL && SL_EHIP == SLORA_EHIP,
+              "internal launcher codes must be the ABI's codes");
+
 
 // ---- descriptor-driven batched kernels (one launch for every adapter of every block) ----------
 struct CastDesc {            // fp32 [rows,cols] (optionally transposed) -> bf16 block [drows,dcols], pitch ld
@@ -49,6 +54,14 @@ __global__ __launch_bounds__(256) void sgd_table_kernel(const SgdDesc *__restric
     const SgdDesc d = tab[blockIdx.y];
     for (int i = blockIdx.x * 256 + threadIdx.x; i < d.n; i += gridDim.x * 256)
         d.p[i] = __fmaf_rn(-lr, d.g[i], d.p[i]);
+}
+
+// A table built on the host reaches the device as kernel arguments (copied when the launch is queued), so no
+// host buffer has to outlive the call, nothing blocks, and the call can be captured into a graph.
+struct TableChunk { uint32_t w[960]; };      // 3840 bytes per launch, within the kernel-argument limit
+__global__ __launch_bounds__(256) void table_upload_kernel(uint32_t *__restrict__ dst, TableChunk c, int nwords)
+{
+    for (int i = threadIdx.x; i < nwords; i += 256) dst[i] = c.w[i];
 }
 
 // ---- error text --------------------------------------------------------------------------------
@@ -256,17 +269,29 @@ int refresh_shadows(slora_ctx *c, hipStream_t st)
     return 0;
 }
 
+int upload_table(void *dst, const void *src, size_t bytes, hipStream_t st)
+{
+    static_assert(sizeof(CastDesc) % 4 == 0 && sizeof(SgdDesc) % 4 == 0, "tables are copied word by word");
+    for (size_t off = 0; off < bytes; off += sizeof(TableChunk)) {
+        const size_t n = bytes - off < sizeof(TableChunk) ? bytes - off : sizeof(TableChunk);
+        TableChunk ch;
+        memcpy(ch.w, (const char *)src + off, n);
+        hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(256), 0, st, (uint32_t *)((char *)dst + off), ch,
+                           (int)(n / 4));
+        SL_CHECK_LAUNCH("table_upload");
+    }
+    return 0;
+}
+
 int prepare(slora_ctx *c, hipStream_t st)
 {
     int rc;
     build_tables(c);
     if (!c->h_cast.empty()) {
-        hipError_t e = hipMemcpyAsync(at<void>(c, c->cast_tab), c->h_cast.data(), sizeof(CastDesc) * c->h_cast.size(),
-                                      hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) { set_hip_error(e, "upload cast table"); return SLORA_EHIP; }
-        e = hipMemcpyAsync(at<void>(c, c->sgd_tab), c->h_sgd.data(), sizeof(SgdDesc) * c->h_sgd.size(),
-                           hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) { set_hip_error(e, "upload sgd table"); return SLORA_EHIP; }
+        if ((rc = upload_table(at<void>(c, c->cast_tab), c->h_cast.data(), sizeof(CastDesc) * c->h_cast.size(), st)))
+            return rc;
+        if ((rc = upload_table(at<void>(c, c->sgd_tab), c->h_sgd.data(), sizeof(SgdDesc) * c->h_sgd.size(), st)))
+            return rc;
         if ((rc = launch_fill_zero(at<void>(c, c->shadow_begin), c->shadow_end - c->shadow_begin, st))) return rc;
     }
     for (int l = 0; l < c->L; ++l) {
@@ -367,11 +392,21 @@ const char *slora_strerror(int code)
 
 const char *slora_last_hip_error(void) { return g_hip_err; }
 
-int slora_prof_enable(int on) { return gemm_prof_enable(on) ? SLORA_EHIP : SLORA_OK; }
+int slora_prof_enable(int kinds)
+{
+    if (kinds < 0 || (kinds >> PK_COUNT)) return SLORA_EINVAL;
+    return prof_enable((unsigned)kinds) ? SLORA_EHIP : SLORA_OK;
+}
+
+int slora_prof_read_kind(int kind, double *h_ms, double *h_work, int *h_launches)
+{
+    if (kind < 0 || kind >= PK_COUNT) return SLORA_EINVAL;
+    return prof_read(kind, h_ms, h_work, h_launches) ? SLORA_EHIP : SLORA_OK;
+}
 
 int slora_prof_read(double *h_gemm_ms, double *h_gemm_flop, int *h_launches)
 {
-    return gemm_prof_read(h_gemm_ms, h_gemm_flop, h_launches) ? SLORA_EHIP : SLORA_OK;
+    return slora_prof_read_kind(SLORA_PROF_GEMM, h_gemm_ms, h_gemm_flop, h_launches);
 }
 
 int slora_create(const slora_config *cfg, slora_ctx **out)
@@ -390,6 +425,10 @@ int slora_create(const slora_config *cfg, slora_ctx **out)
     if (!(cfg->ln_eps > 0.f) || !(cfg->lora_alpha == cfg->lora_alpha)) return SLORA_EINVAL;
     if (cfg->max_seqs <= 0 || cfg->seq_len <= 0 || cfg->seq_len % 64) return SLORA_EINVAL;
     if ((long long)cfg->max_seqs * cfg->seq_len > (1ll << 24)) return SLORA_EINVAL;
+    {   // 32-bit byte offsets into the widest GEMM operand ([T, 3 d_model] or [T, d_ff], bf16)
+        const long long wide = 3ll * cfg->d_model > cfg->d_ff ? 3ll * cfg->d_model : cfg->d_ff;
+        if ((long long)cfg->max_seqs * cfg->seq_len * wide >= (1ll << 31)) return SLORA_EINVAL;
+    }
     slora_ctx *c = new (std::nothrow) slora_ctx();
     if (!c) return SLORA_EINVAL;
     c->cfg = *cfg;
@@ -799,8 +838,12 @@ int slora_adapter_step(slora_ctx *c, float lr, void *stream)
         for (const SgdDesc &d : c->h_sgd) max_n = d.n > max_n ? d.n : max_n;
         int gx = (max_n + 255) / 256;
         if (gx > 64) gx = 64;
+        double n_par = 0.0;
+        for (const SgdDesc &d : c->h_sgd) n_par += d.n;
+        const bool rec = prof_begin(PK_SGD, st);
         hipLaunchKernelGGL(sgd_table_kernel, dim3(gx, (unsigned)c->h_sgd.size()), dim3(256), 0, st,
                            at<SgdDesc>(c, c->sgd_tab), lr);
+        prof_end(rec, PK_SGD, 12.0 * n_par, st);     // parameter and gradient read, parameter written
         SL_CHECK_LAUNCH("sgd_table");
         int rc = refresh_shadows(c, st);
         if (rc) return rc;
@@ -867,6 +910,7 @@ bool lin_args_ok(int dtype, int T, int n_in, int n_out, int r)
     if (dtype != SLORA_DTYPE_F32 && dtype != SLORA_DTYPE_BF16) return false;
     if (T <= 0 || n_in <= 0 || n_out <= 0 || r < 1 || r > SLORA_MAX_RANK) return false;
     if ((long long)T * (n_in > n_out ? n_in : n_out) > (1ll << 31) - 1) return false;
+    if ((long long)n_in * n_out > (1ll << 31) - 1) return false;
     if (dtype == SLORA_DTYPE_BF16 && ((n_in % 64) || (n_out % 64))) return false;
     return true;
 }
@@ -906,8 +950,9 @@ int slora_lora_linear_fwd(int dtype, int T, int n_in, int n_out, int r, float al
 int slora_frozen_linear_bf16(int T, int n_in, int n_out, const void *x, const void *W, const void *bias, void *y,
                              void *stream)
 {
-    if (T <= 0 || n_in <= 0 || n_out <= 0 || (n_in % 64) || !x || !W || !y) return SLORA_EINVAL;
+    if (T <= 0 || n_in <= 0 || n_out <= 0 || (n_in % 64) || (n_out % 8) || !x || !W || !y) return SLORA_EINVAL;
     if ((long long)T * (n_in > n_out ? n_in : n_out) > (1ll << 31) - 1) return SLORA_EINVAL;
+    if ((long long)n_in * n_out > (1ll << 31) - 1) return SLORA_EINVAL;
     if ((((uintptr_t)x) | ((uintptr_t)W) | ((uintptr_t)y)) & 15) return SLORA_EINVAL;
     GemmArgs a = gemm_base((const bf16 *)x, n_in, (const bf16 *)W, T, n_out, n_in, (const bf16 *)bias, 0.f);
     a.out0 = y;

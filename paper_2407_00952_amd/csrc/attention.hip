@@ -6,16 +6,19 @@
 // Layout: qkv [T, 3d] bf16 (q | k | v column blocks, head a at columns 64a..64a+63 of each),
 // o / dO [T, d], lse [n_seq, H, S] fp32 in log2 units of the scaled scores, delta likewise.
 //
-// All three kernels use 4 wavefronts per block, each owning 32 rows (queries or keys), and
-// online-softmax tiles of 64 staged in LDS by asynchronous global->LDS copies, double
-// buffered.  Scores are produced with the lane owning one query (forward, dQ) or one key
-// (dK/dV), which makes the softmax statistics per-lane scalars and lets the probabilities
-// feed the next MFMA straight from registers.  Operands that must be read along the token
-// axis (V, K for dQ, Q and dO for dK/dV) come from the same row-major tiles through the LDS
-// transpose read, so nothing is transposed in memory.
-// The backward is split into a dQ kernel and a dK/dV kernel so that no floating-point
-// atomics are needed and results are bit-reproducible.
+// Forward, and the backward for sequences longer than 512 (a dQ kernel, then a dK/dV kernel): 4 wavefronts
+// per block, each owning 32 rows (queries or keys), online-softmax tiles of 64 staged in LDS by asynchronous
+// global->LDS copies, double buffered.  Scores are produced with the lane owning one query (forward, dQ) or
+// one key (dK/dV), which makes the softmax statistics per-lane scalars and lets the probabilities feed the
+// next MFMA straight from registers.  Operands that must be read along the token axis (V, K for dQ, Q and
+// dO for dK/dV) come from the same row-major tiles through the LDS transpose read, so nothing is
+// transposed in memory.
+// Backward for sequences up to 512 (the default at the paper's sequence length): one block of 8 wavefronts
+// per (sequence, head) forms dQ, dK and dV in one pass; K of the whole sequence stays in LDS, scores,
+// probabilities and dP are formed once (see attn_bwd_fused_kernel).
+// No kernel uses floating-point atomics, so results are bit-reproducible.
 #include "common.h"
+#include "prof.h"
 
 namespace {
 
@@ -690,11 +693,14 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
 
 int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st)
 {
-    if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return -1;
+    if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return SL_EINVAL;
     const long long pairs8 = ((long long)H * n_seq + 7) / 8 * 8;
     const long long nblk = pairs8 * ((S + 127) / 128);
-    if (nblk > 0x7fffffffLL) return -1;
+    if (nblk > 0x7fffffffLL) return SL_EINVAL;
+    // algorithmic work: two products over the lower triangle, 2 S d flop per token (d = 64 H)
+    const bool rec = prof_begin(PK_ATTN_FWD, st);
     hipLaunchKernelGGL(attn_fwd_kernel, dim3((unsigned)nblk), dim3(256), 0, st, qkv, o, o_lo, lse, S, H, n_seq);
+    prof_end(rec, PK_ATTN_FWD, 2.0 * S * 64.0 * H * ((double)n_seq * S), st);
     SL_CHECK_LAUNCH("attn_fwd");
     return 0;
 }
@@ -702,19 +708,24 @@ int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq,
 int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16 *dout, const float *lse,
                     float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st)
 {
-    if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return -1;
+    if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return SL_EINVAL;
+    // algorithmic work: four products over the lower triangle (the recomputed scores are not counted)
+    const double work = 4.0 * S * 64.0 * H * ((double)n_seq * S);
+    const bool rec = prof_begin(PK_ATTN_BWD, st);
     if (S <= FB_MAXS) {
         hipLaunchKernelGGL(attn_bwd_fused_kernel, dim3(H, n_seq), dim3(512), 0, st, qkv, o, o_lo, dout, lse, dqkv, S, H);
+        prof_end(rec, PK_ATTN_BWD, work, st);
         SL_CHECK_LAUNCH("attn_bwd_fused");
         return 0;
     }
     const long long pairs8 = ((long long)H * n_seq + 7) / 8 * 8;
     const long long nblk = pairs8 * ((S + 127) / 128);
-    if (nblk > 0x7fffffffLL) return -1;
+    if (nblk > 0x7fffffffLL) return SL_EINVAL;
     const dim3 grid((unsigned)nblk);
     hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, dout, lse, delta, dqkv, S, H, n_seq);
     SL_CHECK_LAUNCH("attn_bwd_dq");
     hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, dim3(256), 0, st, qkv, dout, lse, delta, dqkv, S, H, n_seq);
+    prof_end(rec, PK_ATTN_BWD, work, st);
     SL_CHECK_LAUNCH("attn_bwd_dkv");
     return 0;
 }

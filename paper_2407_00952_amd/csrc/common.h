@@ -12,6 +12,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+// Return codes of the internal launchers.  They travel unchanged through the C ABI, so they carry the values of
+// SLORA_OK, SLORA_EINVAL and SLORA_EHIP (asserted where the ABI header is included).
+enum { SL_OK = 0, SL_EINVAL = -1, SL_EHIP = -4 };
+
 #define SL_WAVE 64
 #define SL_RP 16            // adapter rank padded to one MFMA k-step
 #define SL_MAX_CLIENTS 64
@@ -130,5 +134,5 @@ const char *set_hip_error(hipError_t e, const char *where);
 #define SL_CHECK_LAUNCH(where)                                          \
     do {                                                                \
         hipError_t e__ = hipGetLastError();                             \
-        if (e__ != hipSuccess) { set_hip_error(e__, where); return -4; } \
+        if (e__ != hipSuccess) { set_hip_error(e__, where); return SL_EHIP; } \
     } while (0)

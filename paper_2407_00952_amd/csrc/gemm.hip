@@ -16,7 +16,7 @@
 // so that both the copies and the MFMA operand reads are bank-conflict free.
 #include "common.h"
 #include "gemm_epilogue.h"
-#include <vector>
+#include "prof.h"
 
 namespace {
 
@@ -24,19 +24,18 @@ constexpr int BM = 256, BN = 256, BK = 64, NTHR = 512;
 constexpr int ROWB = BK * 2;                 // bytes per LDS row (one k-slab of a tile row)
 constexpr int XB = BM * ROWB, WB = BN * ROWB;
 
-// asynchronous global -> LDS copy of 16 bytes per lane: the 64 lanes fill 1 KB starting at `lp`
-#define SL_GLDS(gp, lp)                                                                            \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gp),         \
-                                     (__attribute__((address_space(3))) void *)(lp), 16, 0, 0)
 #define SL_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)   // vmcnt(0): this wave's copies have landed
 
-// The same copy with a scalar 64-bit base and a 32-bit per-lane byte offset, which keeps the address
-// down to one VGPR per row.  `lds` is the wave-uniform LDS byte address the 1 KB lands at.  Waiting
-// for completion (SL_WAIT_VM0 + barrier) is the caller's job, as with the builtin.
+// Asynchronous global -> LDS copy of 16 bytes per lane (the 64 lanes fill 1 KB) with a scalar 64-bit base
+// and a 32-bit per-lane byte offset, which keeps the address down to one VGPR per row.  `lds` is the
+// wave-uniform LDS byte address the 1 KB lands at.  Waiting for completion (SL_WAIT_VM0 + barrier) is
+// the caller's job.
 __device__ __forceinline__ void glds_soff(const void *sbase, unsigned voff, unsigned lds)
 {
-    // M0 carries the LDS address; one wait state is required between its write and the copy.
-    // Nothing else in these kernels uses M0, so it is not listed as clobbered.
+    // M0 carries the LDS address; one wait state is required between its write and the copy.  The compiler
+    // treats M0 as reserved and does not accept it on a clobber list, so nothing else in this file may
+    // depend on M0: tests/test_kernel_isa.py checks in the compiled code that every write of M0 is the one
+    // below and that nothing but these copies reads it.
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds), "v"(voff), "s"(sbase)
@@ -314,9 +313,11 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 // stages: three for the X tile and two for the W tile, so the X copies run two slabs ahead and the W
 // copies one; the 16 copies a wave issues per slab are spread two to a row of 8 MFMAs, because with a
 // single wave per SIMD a burst of copies that fills the memory-issue queue stalls the MFMAs behind it.
-// The MFMA hazards the compiler can no longer see (inline assembly) are covered by construction: an
-// accumulator is reused 64 MFMAs after it was written, fragments come from LDS reads the compiler
-// still tracks, and the accumulators are first read 32 wait states after the last MFMA.
+// The MFMA hazards the compiler can no longer see (inline assembly) are covered by construction: every MFMA
+// accumulates in place (destination = addend, the back-to-back form the hardware interlocks) and the same
+// accumulator comes round again only 64 MFMAs later; fragments come from LDS reads the compiler still
+// tracks; and the only way out of the loop leads through 24 wait states (see the end of the loop body).
+// tests/test_kernel_isa.py verifies all three in the compiled code of every instantiation.
 // ---------------------------------------------------------------------------------------------------
 constexpr int NTHR4 = 256, HB = 32768;       // HB: one operand's k-slab (256 rows x 128 B)
 
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 8; ++i) { G4_LDA(i, 0, 0) G4_LDB(0, i, 3 * HB, 0) }
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = 0;; ++kt) {                            // nk >= 1 (checked by the launcher)
         const int xnxt = xcur == 2 * HB ? 0 : xcur + HB, wnxt = wcur ^ (3 * HB ^ 4 * HB);
         G4_STEP(0, 1, xcur, wcur, 1)                     // MFMAs (slab kt, step 0); fetch (kt, step 1)
         // slab kt+1 has landed (X of kt+2 may still be in flight); nobody reads slab kt's buffers any more
@@ -435,9 +436,14 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         __syncthreads();
         G4_STEPC(1, 0, xnxt, wnxt, 0, min((kt + 2) * BK, klast), min((kt + 3) * BK, klast))
         xcur = xnxt; wcur = wnxt;
-        // after the last slab, still inside the loop body: the last MFMAs retire before anything the
-        // compiler places behind the loop can read an accumulator (it takes them for finished)
-        if (kt + 1 >= nk) asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+        // The compiler takes an accumulator for finished where its MFMA is issued, and it moves accumulators
+        // between registers right where the loop ends.  The only way out of the loop is through these wait
+        // states, which let the last MFMAs retire first (a 16-pass result needs 19;
+        // tests/test_kernel_isa.py follows every path from the last MFMA in the compiled code).
+        if (kt + 1 >= nk) {
+            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+            break;
+        }
     }
 #undef G4_COPYX
 #undef G4_COPYW
@@ -446,14 +452,9 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 #undef G4_ROW
 #undef G4_STEP
 #undef G4_STEPC
-    // all copies have landed and every wave is out of the loop before the ring is reused; the wait
-    // states let the last MFMAs retire before their accumulators are read
+    // all copies have landed and every wave is out of the loop before the ring is reused
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
-    asm volatile("s_nop 15\n\ts_nop 15"
-                 : "+a"(acc[7][0]), "+a"(acc[7][1]), "+a"(acc[7][2]), "+a"(acc[7][3]), "+a"(acc[7][4]),
-                   "+a"(acc[7][5]), "+a"(acc[7][6]), "+a"(acc[7][7]));
-
     // ---- epilogue: as in the 8-wave kernel, 32 x 64 strips transposed through a private LDS strip;
     //      a wave tile is 4 row strips x 2 column halves
     constexpr int EP = 68;
@@ -546,64 +547,20 @@ int launch_e(const GemmArgs &a, int nz, hipStream_t st)
     case 32: return launch_t<EPI, 32>(a, st);
     case 48: return launch_t<EPI, 48>(a, st);
     }
-    return -1;
+    return SL_EINVAL;
 }
-
-// ---- optional timing of the GEMM launches with HIP events (measurement hook) ---------------------
-struct GemmProf {
-    bool on = false;
-    std::vector<hipEvent_t> ev;      // pairs: start, stop
-    size_t used = 0;
-    double flop = 0.0;
-} g_prof;
 
 }  // namespace
-
-int gemm_prof_enable(int on)
-{
-    if (on && g_prof.ev.empty()) {
-        g_prof.ev.resize(16384);
-        for (auto &e : g_prof.ev)
-            if (hipEventCreate(&e) != hipSuccess) { g_prof.ev.clear(); return -4; }
-    }
-    g_prof.on = on != 0;
-    g_prof.used = 0;
-    g_prof.flop = 0.0;
-    return 0;
-}
-
-int gemm_prof_read(double *ms, double *flop, int *launches)
-{
-    double tot = 0.0;
-    for (size_t i = 0; i + 1 < g_prof.used; i += 2) {
-        float t = 0.f;
-        if (hipEventSynchronize(g_prof.ev[i + 1]) != hipSuccess) return -4;
-        if (hipEventElapsedTime(&t, g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess) return -4;
-        tot += t;
-    }
-    if (ms) *ms = tot;
-    if (flop) *flop = g_prof.flop;
-    if (launches) *launches = (int)(g_prof.used / 2);
-    g_prof.used = 0;
-    g_prof.flop = 0.0;
-    return 0;
-}
 
 static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st);
 
 int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st)
 {
-    const bool rec = g_prof.on && g_prof.used + 2 <= g_prof.ev.size();
-    if (rec) (void)hipEventRecord(g_prof.ev[g_prof.used], st);
+    const bool rec = prof_begin(PK_GEMM, st);
     const int rc = launch_gemm_inner(a, epi, nz, st);
-    if (rec) {
-        (void)hipEventRecord(g_prof.ev[g_prof.used + 1], st);
-        g_prof.used += 2;
-        // algorithmic work of this launch: the frozen product only (the rank-r branch adds < 1 %
-        // and is left out, which understates the achieved rate slightly)
-        const double f = 2.0 * a.M * (double)a.N * a.K;
-        g_prof.flop += f;
-    }
+    // algorithmic work of this launch: the frozen product only (the rank-r branch adds < 1 % and is left
+    // out, which understates the achieved rate slightly)
+    prof_end(rec, PK_GEMM, 2.0 * a.M * (double)a.N * a.K, st);
     return rc;
 }
 
@@ -611,17 +568,17 @@ static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K % BK) != 0 || a.nseg < 1 || a.nseg > 3 ||
         a.nseg * a.seg_n != a.N || (a.ldx % 8) || (a.ldw % 8) || (a.seg_n % 8) || (a.ldo % 8))
-        return -1;
+        return SL_EINVAL;
     if (a.mx) return launch_gemm_mx_stack(a, epi, nz, st);
     // the copies address both operands with 32-bit byte offsets from their bases
     if ((unsigned long long)a.M * a.ldx * 2ull >= (1ull << 32) || (unsigned long long)a.N * a.ldw * 2ull >= (1ull << 32))
-        return -1;
-    if (nz > 0 && (a.K2 != nz || (a.ldt % 8) || a.ldt < (nz + 31) / 32 * 32 || (a.ldz % 8))) return -1;
+        return SL_EINVAL;
+    if (nz > 0 && (a.K2 != nz || (a.ldt % 8) || a.ldt < (nz + 31) / 32 * 32 || (a.ldz % 8))) return SL_EINVAL;
     switch (epi) {
     case EPI_STORE: return launch_e<EPI_STORE>(a, nz, st);
     case EPI_RESID: return launch_e<EPI_RESID>(a, nz, st);
     case EPI_GELU: return launch_e<EPI_GELU>(a, nz, st);
     case EPI_DGELU: return launch_e<EPI_DGELU>(a, nz, st);
     }
-    return -1;
+    return SL_EINVAL;
 }

@@ -11,6 +11,7 @@
 //  * SGD (Eq. 4-5): p = fmaf(-lr, g, p).
 //  * FedAvg (Sec. III-B step b2, Eq. 8-9): acc = fmaf(w_i, x_i[j], acc), i = 0..K-1.
 #include "common.h"
+#include "prof.h"
 
 namespace {
 
@@ -325,10 +326,13 @@ size_t lora_grad_partial_floats(int T, int C)
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
                      float *out, int out_is_rxC, hipStream_t st)
 {
-    if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || r < 1 || r > 16) return -1;
+    if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || r < 1 || r > 16) return SL_EINVAL;
     const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
     dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
+    // algorithmic bytes of the streaming pass: the tall operand once, the skinny one once per column block
+    const bool rec = prof_begin(PK_LORA_GRAD, st);
     hipLaunchKernelGGL((lora_grad_partial_kernel<false>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
+    prof_end(rec, PK_LORA_GRAD, 2.0 * T * (double)C, st);
     SL_CHECK_LAUNCH("lora_grad_partial");
     hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
                        out, (float *)nullptr, out_is_rxC);
@@ -341,10 +345,12 @@ int launch_lora_grad_pair(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy,
                           float *out_a, float *out_b, int out_is_rxC, hipStream_t st)
 {
     if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || ldy < 32 || r < 1 || r > 16 || !out_a || !out_b)
-        return -1;
+        return SL_EINVAL;
     const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
     dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
+    const bool rec = prof_begin(PK_LORA_GRAD, st);
     hipLaunchKernelGGL((lora_grad_partial_kernel<true>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
+    prof_end(rec, PK_LORA_GRAD, 2.0 * T * (double)C, st);
     SL_CHECK_LAUNCH("lora_grad_partial");
     hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((2 * r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
                        out_a, out_b, out_is_rxC);
@@ -417,8 +423,10 @@ int launch_fedavg(int K, const float *const *x, const float *w, size_t n, float 
     size_t blocks = (work + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 16384) blocks = 16384;
+    const bool rec = prof_begin(PK_FEDAVG, st);
     if (vec) hipLaunchKernelGGL((fedavg_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, t, n, out);
     else hipLaunchKernelGGL((fedavg_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, t, n, out);
+    prof_end(rec, PK_FEDAVG, 4.0 * (K + 1) * (double)n, st);
     SL_CHECK_LAUNCH("fedavg");
     return 0;
 }

@@ -459,7 +459,7 @@ int launch_gemm_mx(const MxArgs &a, hipStream_t st, bool w4 = false, int epi = E
     const int nb = ((a.M + BM - 1) / BM) * (((a.seg_n + BN - 1) / BN) * a.nseg);
     const dim3 grid(((nb + 7) / 8) * 8), block(NTHR);
     if (w4) {
-        if (epi != EPI_STORE) return -1;
+        if (epi != EPI_STORE) return SL_EINVAL;
         hipLaunchKernelGGL((gemm_mx_kernel<true, EPI_STORE>), grid, block, 0, st, a);
     } else {
         switch (epi) {
@@ -467,7 +467,7 @@ int launch_gemm_mx(const MxArgs &a, hipStream_t st, bool w4 = false, int epi = E
         case EPI_RESID: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_RESID>), grid, block, 0, st, a); break;
         case EPI_GELU: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_GELU>), grid, block, 0, st, a); break;
         case EPI_DGELU: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_DGELU>), grid, block, 0, st, a); break;
-        default: return -1;
+        default: return SL_EINVAL;
         }
     }
     SL_CHECK_LAUNCH("gemm_mx");
@@ -499,7 +499,7 @@ int launch_rank_project(const bf16 *X, long long ldx, int M, int K, const bf16 *
     case 16: hipLaunchKernelGGL((rank_project_kernel<1>), grid, block, 0, st, X, ldx, M, K, Z, ldz, scale, out); break;
     case 32: hipLaunchKernelGGL((rank_project_kernel<2>), grid, block, 0, st, X, ldx, M, K, Z, ldz, scale, out); break;
     case 48: hipLaunchKernelGGL((rank_project_kernel<3>), grid, block, 0, st, X, ldx, M, K, Z, ldz, scale, out); break;
-    default: return -1;
+    default: return SL_EINVAL;
     }
     SL_CHECK_LAUNCH("rank_project");
     return 0;
@@ -555,34 +555,34 @@ bool mx_lin_args_ok(int T, int n_in, int n_out, int r)
 int launch_mx_quantize(const bf16 *x, long long ldx, long long M, int K, unsigned char *codes, unsigned char *scales,
                        hipStream_t st)
 {
-    if (M <= 0 || K <= 0 || (K % 32) || ldx < K) return -1;
+    if (M <= 0 || K <= 0 || (K % 32) || ldx < K) return SL_EINVAL;
     return launch_quantize(x, ldx, M, K, codes, scales, st);
 }
 
 int launch_gemm_mx_stack(const GemmArgs &g, int epi, int nz, hipStream_t st)
 {
     const MxOperands &m = *g.mx;
-    if ((g.K % 128) || (g.seg_n % 8) || g.ldw != g.K || !m.wq || !m.ws || !m.xq || !m.xs) return -1;
-    if ((unsigned long long)g.M * g.K >= (1ull << 32) || (unsigned long long)g.N * g.K >= (1ull << 32)) return -1;
+    if ((g.K % 128) || (g.seg_n % 8) || g.ldw != g.K || !m.wq || !m.ws || !m.xq || !m.xs) return SL_EINVAL;
+    if ((unsigned long long)g.M * g.K >= (1ull << 32) || (unsigned long long)g.N * g.K >= (1ull << 32)) return SL_EINVAL;
     int rc;
-    if (!m.x_ready && !g.X) return -1;
+    if (!m.x_ready && !g.X) return SL_EINVAL;
     if (!m.x_ready && (rc = launch_quantize(g.X, g.ldx, g.M, g.K, m.xq, m.xs, st))) return rc;
     MxArgs a = mx_plain(m.xq, m.xs, m.wq, m.ws, g.bias, g.out0, g.M, g.N, g.K);
     a.nseg = g.nseg; a.seg_n = g.seg_n;
     a.out1 = g.out1; a.aux = g.aux; a.ldo = g.ldo;
     if (g.oq) {
-        if (!g.os || (g.ldo % 32) || (g.seg_n % 32) || (epi != EPI_GELU && epi != EPI_DGELU)) return -1;
+        if (!g.os || (g.ldo % 32) || (g.seg_n % 32) || (epi != EPI_GELU && epi != EPI_DGELU)) return SL_EINVAL;
         a.oq = g.oq; a.os = g.os;
     }
     // the bf16 copy of the tensor that also goes out as codes may be left out; everything else must exist
     if (!(epi == EPI_GELU ? g.out0 && (g.out1 || g.oq) : epi == EPI_DGELU ? (g.out0 || g.oq) : g.out0 || g.out1))
-        return -1;
+        return SL_EINVAL;
     if (nz > 0) {
         a.K2 = g.K2; a.ldt = g.ldt;
         for (int sgm = 0; sgm < g.nseg; ++sgm) {
             if (!g.zmat[sgm]) continue;
             // the bf16 kernel forms these inside its K loop from the bf16 tile; here the tile is fp8
-            if (!g.zspill[sgm] || !g.tmat[sgm] || !g.X) return -1;
+            if (!g.zspill[sgm] || !g.tmat[sgm] || !g.X) return SL_EINVAL;
             if ((rc = launch_rank_project(g.X, g.ldx, g.M, g.K, g.zmat[sgm], g.ldz, nz, g.zscale, g.zspill[sgm], st)))
                 return rc;
             a.zs[sgm] = g.zspill[sgm];

@@ -14,6 +14,7 @@
 //             per-client activation gradient scattered back to the K client buffers).
 #include "common.h"
 #include "mx_codec.h"
+#include "prof.h"
 
 namespace {
 
@@ -238,17 +239,20 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, 
                   const bf16 *beta, float eps, bf16 *u, float *stats, int T, int d, hipStream_t st,
                   const EmbedSrc *embed, unsigned char *u_codes, unsigned char *u_scales)
 {
-    if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
-    if (u_codes && (!u_scales || (d % 32))) return -1;
-    if (!u && !u_codes) return -1;
-    if (gather && gather->mx && (d % 32)) return -1;
+    if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return SL_EINVAL;
+    if (u_codes && (!u_scales || (d % 32))) return SL_EINVAL;
+    if (!u && !u_codes) return SL_EINVAL;
+    if (gather && gather->mx && (d % 32)) return SL_EINVAL;
     dim3 grid((T + 3) / 4), block(256);
     ClientTable none;
     none.K = 0;
     none.mx = 0;
     EmbedSrc noemb = {nullptr, nullptr, nullptr, 1, 1};
+    // algorithmic bytes: the row read once (fp32, or bf16 / codes when gathered, then also kept as fp32), u written
+    const double row_bytes = (embed ? 4 + 4 : gather ? (gather->mx ? 1 + 4 : 2 + 4) : 4) + (u ? 2 : 0) + (u_codes ? 1 : 0);
+    const bool rec = prof_begin(PK_LN_FWD, st);
     if (embed) {
-        if (!embed->tokens || !embed->wte || !embed->wpe || embed->seq_len <= 0 || embed->vocab <= 0) return -1;
+        if (!embed->tokens || !embed->wte || !embed->wpe || embed->seq_len <= 0 || embed->vocab <= 0) return SL_EINVAL;
         hipLaunchKernelGGL((ln_fwd_kernel<2>), grid, block, 0, st, nullptr, none, *embed, h_copy, gamma, beta, eps, u,
                            stats, T, d, u_codes, u_scales);
     } else if (gather && gather->mx) {
@@ -261,6 +265,7 @@ int launch_ln_fwd(const float *h_f32, const ClientTable *gather, float *h_copy, 
         hipLaunchKernelGGL((ln_fwd_kernel<0>), grid, block, 0, st, h_f32, none, noemb, nullptr, gamma, beta, eps, u,
                            stats, T, d, u_codes, u_scales);
     }
+    prof_end(rec, PK_LN_FWD, row_bytes * (double)T * d, st);
     SL_CHECK_LAUNCH("ln_fwd");
     return 0;
 }
@@ -269,16 +274,20 @@ int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16
                   const bf16 *dres_bf16, float *out_f32, bf16 *out_bf16, const ClientTable *scatter, int T, int d,
                   hipStream_t st, unsigned char *o_codes, unsigned char *o_scales)
 {
-    if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return -1;
-    if (o_codes && (!o_scales || (d % 32) || scatter)) return -1;
+    if (T <= 0 || d <= 0 || (d % 4) || d > MAXC * 256) return SL_EINVAL;
+    if (o_codes && (!o_scales || (d % 32) || scatter)) return SL_EINVAL;
     dim3 grid((T + 3) / 4), block(256);
     ClientTable tab;
     tab.K = 0;
     tab.mx = 0;
     if (scatter) tab = *scatter;
+    // algorithmic bytes per element: du (bf16), h (fp32), the residual gradient, and each output written
+    const double el_bytes = 2 + 4 + (dres_bf16 ? 2 : dres_f32 ? 4 : 0) + (out_f32 ? 4 : 0) + (out_bf16 ? 2 : 0) +
+                            (scatter ? (scatter->mx ? 1 : 2) : 0) + (o_codes ? 1 : 0);
+    const bool rec = prof_begin(PK_LN_BWD, st);
     if (scatter && scatter->mx) {
         // compressed activation gradients: only the first server block scatters, and its residual gradient is fp32
-        if ((d % 32) || dres_bf16) return -1;
+        if ((d % 32) || dres_bf16) return SL_EINVAL;
         hipLaunchKernelGGL((ln_bwd_kernel<false, 2>), grid, block, 0, st, du, h, stats, gamma, (const void *)dres_f32,
                            out_f32, out_bf16, tab, T, d, o_codes, o_scales);
     } else if (dres_bf16) {
@@ -296,6 +305,7 @@ int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16
             hipLaunchKernelGGL((ln_bwd_kernel<false, 0>), grid, block, 0, st, du, h, stats, gamma,
                                (const void *)dres_f32, out_f32, out_bf16, tab, T, d, o_codes, o_scales);
     }
+    prof_end(rec, PK_LN_BWD, el_bytes * (double)T * d, st);
     SL_CHECK_LAUNCH("ln_bwd");
     return 0;
 }

@@ -147,6 +147,33 @@ def test_linear_argument_checks():
     assert e.value.code == B.SLORA_EINVAL
 
 
+def test_documented_size_limits_are_enforced():
+    # the frozen product: out a multiple of 8, in a multiple of 64, operands within 32-bit byte offsets
+    for T, n_in, n_out in ((64, 64, 100), (64, 100, 64), (1 << 20, 4096, 64), (64, 65536, 65536)):
+        with pytest.raises(B.SloraError) as e:
+            B.slora_frozen_linear_bf16(T, n_in, n_out, FAKE, FAKE, None, FAKE, stream=0)
+        assert e.value.code == B.SLORA_EINVAL, (T, n_in, n_out)
+    assert B.slora_lora_linear_ws_bytes(B.DTYPE_BF16, 64, 65536, 65536, 4) == 0
+    # contexts: width above 2048, token count above 2^24, widest operand beyond 32-bit byte offsets
+    for bad in (dict(d_model=2112, n_head=33), dict(max_seqs=1 << 16, seq_len=512),
+                dict(d_model=2048, n_head=32, d_ff=8192, max_seqs=512, seq_len=1024)):
+        with pytest.raises(B.SloraError) as e:
+            _create(**bad)
+        assert e.value.code == B.SLORA_EINVAL, bad
+    B.slora_destroy(_create(d_model=2048, n_head=32, d_ff=8192, max_seqs=255, seq_len=1024))
+
+
+def test_measurement_hook_argument_checks():
+    with pytest.raises(B.SloraError) as e:
+        B.slora_prof_enable(1 << B.PROF_KINDS)
+    assert e.value.code == B.SLORA_EINVAL
+    with pytest.raises(B.SloraError) as e:
+        B.slora_prof_read_kind(B.PROF_KINDS)
+    assert e.value.code == B.SLORA_EINVAL
+    B.slora_prof_enable(0)
+    assert B.slora_prof_read_kind(B.PROF_LN_FWD) == (0.0, 0.0, 0)
+
+
 def test_loss_head_argument_checks():
     n = B.slora_loss_head_ws_bytes(32768, 1024, 50257)
     # two copies of the padded vocabulary matrix + one 16384-token chunk of bf16 logits + per-token buffers
