@@ -152,6 +152,21 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
                           const void *x, const void *dy, const void *W, const float *A, const float *B,
                           void *dx, float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): slora_lora_linear_bwd for dtype BF16 with the scratch held inside the
+ * library, in one fixed array of SLORA_NOALLOC_SCRATCH_BYTES per GPU that stays allocated until the process
+ * ends.  Same arguments (minus dtype and the workspace), same kernels, same results as
+ * slora_lora_linear_bwd.  Calls nothing that allocates or frees.  SLORA_ENOSPC when
+ * slora_lora_linear_ws_bytes(SLORA_DTYPE_BF16, T, n_in, n_out, r) exceeds SLORA_NOALLOC_SCRATCH_BYTES (e.g.
+ * T = 4096 with n_in = n_out = 1024 needs 11.3 MiB); SLORA_EINVAL / SLORA_EHIP as for slora_lora_linear_bwd.
+ * All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU (different
+ * streams, or different host threads) race; calls queued on one stream are safe.  Nothing in the array has
+ * to be cleared between calls. */
+#define SLORA_NOALLOC_SCRATCH_BYTES (32 << 20)
+int slora_lora_linear_bwd_noalloc(int T, int n_in, int n_out, int r, float alpha,
+                                  const void *x, const void *dy, const void *W, const float *A, const float *B,
+                                  void *dx, float *dA, float *dB, void *stream);
+
 /* The frozen product alone (Sec. II-C with no adapter): y [T,out] = x [T,in] W[out,in]^T + bias, all
  * bf16 with fp32 accumulation; bias may be NULL.  in a multiple of 64, out a multiple of 8; x, W, y 16-byte
  * aligned; T * max(in, out) < 2^31 and in * out < 2^31 elements (SLORA_EINVAL otherwise).  Runs the same GEMM

@@ -32,7 +32,8 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_frozen_linear_mxfp8", "slora_mx_weight_bytes", "slora_mx_pack_weight",
            "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd",
            "slora_server_fwd_mx", "slora_server_bwd_mx", "slora_mx_quantize_fp4",
-           "slora_frozen_linear_mxfp8_w4", "slora_prof_read_kind"]
+           "slora_frozen_linear_mxfp8_w4", "slora_lora_linear_bwd_noalloc", "slora_prof_read_kind"]
+NOALLOC_SCRATCH_BYTES = 32 << 20
 (PROF_GEMM, PROF_LN_FWD, PROF_LN_BWD, PROF_LORA_GRAD, PROF_SGD, PROF_ATTN_FWD, PROF_ATTN_BWD, PROF_FEDAVG,
  PROF_KINDS) = range(9)
 
@@ -76,6 +77,7 @@ def lib():
         L.slora_lora_linear_ws_bytes.restype = sz
         L.slora_lora_linear_fwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slora_lora_linear_bwd.argtypes = [i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slora_lora_linear_bwd_noalloc.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.slora_frozen_linear_bf16.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
         L.slora_client_fwd.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
         L.slora_client_bwd.argtypes = [vp, vp, vp]
@@ -213,6 +215,11 @@ def slora_lora_linear_fwd(dtype, T, n_in, n_out, r, alpha, x, W, bias, A, B, y, 
 def slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, dA, dB, ws, ws_bytes, stream=None):
     _check(lib().slora_lora_linear_bwd(dtype, T, n_in, n_out, r, alpha, _p(x), _p(dy), _p(W), _p(A), _p(B),
                                        _p(dx), _p(dA), _p(dB), _p(ws), ws_bytes, _stream(stream)))
+
+
+def slora_lora_linear_bwd_noalloc(T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, dA, dB, stream=None):
+    _check(lib().slora_lora_linear_bwd_noalloc(T, n_in, n_out, r, alpha, _p(x), _p(dy), _p(W), _p(A), _p(B), _p(dx),
+                                               _p(dA), _p(dB), _stream(stream)))
 
 
 def slora_frozen_linear_bf16(T, n_in, n_out, x, W, bias, y, stream=None):

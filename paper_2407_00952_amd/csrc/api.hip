@@ -993,4 +993,50 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
     return launch_lora_grad((const bf16 *)dy, n_out, n_out, (bf16 *)(base + w.zs), 16, r, T, part, dB, 0, st);
 }
 
+// ---- the same backward for callers that cannot allocate ------------------------------------------
+// The scratch of slora_lora_linear_bwd held by the library itself: one array per GPU (every device the
+// code object is loaded on has its own copy at its own address), alive until the process ends.
+static __device__ __align__(256) unsigned char scratch[SLORA_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each GPU, null until first use there
+
+// `scratch` is a host-side stand-in in host code, not a device address: ask the runtime for the address
+// on the current device once and use only that pointer afterwards.
+int scratch_address(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_hip_error(e, "hipGetDevice"); return SLORA_EHIP; }
+    if (dev < 0 || dev >= kMaxDevices) return SLORA_EINVAL;
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) { set_hip_error(e, "hipGetSymbolAddress(scratch)"); return SLORA_EHIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SLORA_OK;
+}
+}  // namespace
+
+int slora_lora_linear_bwd_noalloc(int T, int n_in, int n_out, int r, float alpha, const void *x, const void *dy,
+                                  const void *W, const float *A, const float *B, void *dx, float *dA, float *dB,
+                                  void *stream)
+{
+    if (!lin_args_ok(SLORA_DTYPE_BF16, T, n_in, n_out, r) || !x || !dy || !W || !A || !B || !dx || !dA || !dB)
+        return SLORA_EINVAL;
+    if (slora_lora_linear_ws_bytes(SLORA_DTYPE_BF16, T, n_in, n_out, r) > (size_t)SLORA_NOALLOC_SCRATCH_BYTES)
+        return SLORA_ENOSPC;
+    if ((((uintptr_t)x) | ((uintptr_t)W) | ((uintptr_t)dy) | ((uintptr_t)dx)) & 15) return SLORA_EINVAL;
+    void *ptr = nullptr;
+    int rc = scratch_address(&ptr);
+    if (rc) return rc;
+    // every region of the scratch that a kernel of this call reads is written earlier in the same call
+    // (padded operand copies are written whole, zeros included), so nothing has to be cleared between calls
+    return slora_lora_linear_bwd(SLORA_DTYPE_BF16, T, n_in, n_out, r, alpha, x, dy, W, A, B, dx, dA, dB, ptr,
+                                 (size_t)SLORA_NOALLOC_SCRATCH_BYTES, stream);
+}
+
 }  // extern "C"

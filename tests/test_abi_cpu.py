@@ -163,6 +163,25 @@ def test_documented_size_limits_are_enforced():
     B.slora_destroy(_create(d_model=2048, n_head=32, d_ff=8192, max_seqs=255, seq_len=1024))
 
 
+def test_noalloc_backward_argument_checks():
+    # checked before anything touches a GPU: sizes beyond the library's own scratch, bad pointers and sizes
+    assert B.slora_lora_linear_ws_bytes(B.DTYPE_BF16, 65536, 4096, 4096, 4) > B.NOALLOC_SCRATCH_BYTES
+    with pytest.raises(B.SloraError) as e:
+        B.slora_lora_linear_bwd_noalloc(65536, 4096, 4096, 4, 32.0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                        stream=0)
+    assert e.value.code == B.SLORA_ENOSPC
+    with pytest.raises(B.SloraError) as e:
+        B.slora_lora_linear_bwd_noalloc(64, 100, 64, 4, 32.0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, stream=0)
+    assert e.value.code == B.SLORA_EINVAL
+    with pytest.raises(B.SloraError) as e:
+        B.slora_lora_linear_bwd_noalloc(64, 64, 64, 4, 32.0, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, stream=0)
+    assert e.value.code == B.SLORA_EINVAL
+    with pytest.raises(B.SloraError) as e:
+        B.slora_lora_linear_bwd_noalloc(64, 64, 64, 4, 32.0, FAKE + 8, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                        stream=0)
+    assert e.value.code == B.SLORA_EINVAL
+
+
 def test_measurement_hook_argument_checks():
     with pytest.raises(B.SloraError) as e:
         B.slora_prof_enable(1 << B.PROF_KINDS)
