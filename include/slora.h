@@ -158,7 +158,7 @@ int slora_lora_linear_bwd(int dtype, int T, int n_in, int n_out, int r, float al
  * ends.  Same arguments (minus dtype and the workspace), same kernels, same results as
  * slora_lora_linear_bwd.  Calls nothing that allocates or frees.  SLORA_ENOSPC when
  * slora_lora_linear_ws_bytes(SLORA_DTYPE_BF16, T, n_in, n_out, r) exceeds SLORA_NOALLOC_SCRATCH_BYTES (e.g.
- * T = 4096 with n_in = n_out = 1024 needs 11.3 MiB); SLORA_EINVAL / SLORA_EHIP as for slora_lora_linear_bwd.
+ * T = 4096 with n_in = n_out = 1024 needs 11.4 MiB, T = 16384 needs 39.2 MiB); SLORA_EINVAL / SLORA_EHIP as for slora_lora_linear_bwd.
  * All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU (different
  * streams, or different host threads) race; calls queued on one stream are safe.  Nothing in the array has
  * to be cleared between calls. */
