@@ -17,6 +17,7 @@
 #include "common.h"
 #include "gemm_epilogue.h"
 #include "prof.h"
+#include <algorithm>
 
 namespace {
 
@@ -313,6 +314,8 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 // stages: three for the X tile and two for the W tile, so the X copies run two slabs ahead and the W
 // copies one; the 16 copies a wave issues per slab are spread two to a row of 8 MFMAs, because with a
 // single wave per SIMD a burst of copies that fills the memory-issue queue stalls the MFMAs behind it.
+// The grid is one block per CU and a block walks its tiles itself, so that the first copies of the next
+// tile are in flight under the epilogue of the current one.
 // The MFMA hazards the compiler can no longer see (inline assembly) are covered by construction: every MFMA
 // accumulates in place (destination = addend, the back-to-back form the hardware interlocks) and the same
 // accumulator comes round again only 64 MFMAs later; fragments come from LDS reads the compiler still
@@ -320,6 +323,61 @@ __global__ __launch_bounds__(NTHR) void gemm_kernel(GemmArgs a)
 // tests/test_kernel_isa.py verifies all three in the compiled code of every instantiation.
 // ---------------------------------------------------------------------------------------------------
 constexpr int NTHR4 = 256, HB = 32768;       // HB: one operand's k-slab (256 rows x 128 B)
+constexpr int EP4 = 68;                      // pitch (floats) of an epilogue staging strip: bank-conflict free
+
+// Epilogue of one 128 x 128 wave tile: 16 strips of 16 rows x 64 columns, each transposed through the wave's
+// private LDS strip `stg` so that global memory sees 16-byte accesses.  INTERIOR (the tile lies wholly inside
+// the matrix: every tile at the model's shapes) has no branch at all, so the compiler waits for exactly the
+// loads a strip needs (partial vmcnt counts) instead of draining every load and store at each predicated
+// block; the operands that come from global memory are requested four strips ahead.
+template <int EPI, bool INTERIOR>
+__device__ __forceinline__ void epilogue4(const GemmArgs &a, f32x4 (&acc)[8][8], float *stg, int m0, int n0,
+                                          int n_end, int wm, int wn, int lane)
+{
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int er = lane >> 3, ec = (lane & 7) * 8;
+    const int row_base = m0 + wm * 128 + er;
+    constexpr int AHEAD = 4;
+    AuxRow aux[16][2];
+    float bias8[2][8];
+#pragma unroll
+    for (int jh = 0; jh < 2; ++jh) {
+        const int gcol = n0 + wn * 128 + jh * 64 + ec;
+        bf16x8 b8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b8[i] = f2bf(0.f);
+        if (a.bias && (INTERIOR || gcol < n_end)) b8 = *(const bf16x8 *)(a.bias + gcol);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bias8[jh][i] = bf2f(b8[i]);
+    }
+#define E4_AUX(s_)                                                                                     \
+    _Pragma("unroll") for (int it = 0; it < 2; ++it) {                                                 \
+        const int row_ = row_base + ((s_) & 7) * 16 + it * 8, col_ = n0 + wn * 128 + ((s_) >> 3) * 64 + ec; \
+        load_aux<EPI>(a, row_, col_, INTERIOR || (row_ < a.M && col_ < n_end), aux[s_][it]);           \
+    }
+#pragma unroll
+    for (int s = 0; s < AHEAD; ++s) E4_AUX(s)
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {                       // strip s: column half s >> 3, rows 16 (s & 7) ..
+        const int jh = s >> 3, i = s & 7;
+        if (s + AHEAD < 16) E4_AUX(s + AHEAD)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) stg[(4 * kg + e) * EP4 + j * 16 + r16] = acc[i][jh * 4 + j][e];
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int rl = it * 8 + er;
+            const float4 p0 = *(const float4 *)(stg + rl * EP4 + ec);
+            const float4 p1 = *(const float4 *)(stg + rl * EP4 + ec + 4);
+            float v[8] = {p0.x + bias8[jh][0], p0.y + bias8[jh][1], p0.z + bias8[jh][2], p0.w + bias8[jh][3],
+                          p1.x + bias8[jh][4], p1.y + bias8[jh][5], p1.z + bias8[jh][6], p1.w + bias8[jh][7]};
+            const int row = m0 + wm * 128 + i * 16 + rl, gcol = n0 + wn * 128 + jh * 64 + ec;
+            if (INTERIOR || (row < a.M && gcol < n_end)) store_row8<EPI>(a, row, gcol, v, aux[s][it]);
+        }
+    }
+#undef E4_AUX
+}
 
 template <int EPI>
 __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel4(GemmArgs a)
@@ -331,120 +389,153 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int wm = wave >> 1, wn = wave & 1;
     const int r16 = lane & 15, kg = lane >> 4;
 
-    // tile of this block: the same XCD-aware panel walk as the 8-wave kernel
+    // Tiles of this block.  The grid is at most one block per CU and a block walks its share of the tiles
+    // itself: blocks are handed to the 8 XCDs round-robin, XCD x owns the logical tiles
+    // [x per_xcd, (x + 1) per_xcd) and its blocks take them in turn, so that the tiles in flight on an XCD are
+    // consecutive ones of the same panel walk as in the 8-wave kernel (a 4 x 8 patch per XCD's L2).  Owning
+    // the CU for the whole launch is what lets the first copies of the next tile run under the epilogue of
+    // the current one (2.5 us per tile otherwise, a tenth of a K = 1024 tile).
     const int tiles_n_seg = (a.seg_n + BN - 1) / BN;
     const int tiles_n = tiles_n_seg * a.nseg;
     const int tiles_m = (a.M + BM - 1) / BM;
     const int nb = tiles_m * tiles_n;
     const int per_xcd = (nb + 7) >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= nb) return;
-    constexpr int PANEL = 4;
-    const int pidx = logical / (PANEL * tiles_n), prem = logical - pidx * (PANEL * tiles_n);
-    const int prow = min(PANEL, tiles_m - pidx * PANEL);
-    const int tn = prem / prow, tm = pidx * PANEL + prem - tn * prow;
-    const int seg = tn / tiles_n_seg;
-    const int tns = tn % tiles_n_seg;
-    const int n0 = seg * a.seg_n + tns * BN;
-    const int n_end = (seg + 1) * a.seg_n;
-    const int m0 = tm * BM;
-
-    // every wave copies 64 rows of each operand tile per slab, 8 rows (1 KB) per instruction; lane l
-    // fills 16-byte slot l: row l>>3, physical k-chunk l&7 holding logical chunk (l&7) ^ (l>>3)
+    const int slots = gridDim.x >> 3;
+    const int t_end = min(((int)(blockIdx.x & 7) + 1) * per_xcd, nb);
+    int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= t_end) return;
     const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
-    unsigned xo[8], wo[8];
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        const int row = min(m0 + wave * 64 + p * 8 + lrow, a.M - 1);
-        const int n = min(n0 + wave * 64 + p * 8 + lrow, n_end - 1);
-        xo[p] = ((unsigned)row * (unsigned)a.ldx + lch * 8) * 2u;
-        wo[p] = ((unsigned)n * (unsigned)a.ldw + lch * 8) * 2u;
-    }
     const char *Xb = (const char *)a.X, *Wb = (const char *)a.W;
     const unsigned ringa = lds_addr(ring) + wave * 64 * ROWB;
-
-    f32x4 acc[8][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
-
     const int a_row = (wm * 128 + r16) * ROWB, b_row = (wn * 128 + r16) * ROWB;
     const int sw = r16 & 7;
-    bf16x8 fa[8], fb[2][8];
+    const int nk = a.K / BK, klast = (nk - 1) * BK;
+    const int k1 = min(BK, klast), k2 = min(2 * BK, klast);
+    // the epilogue's staging strips live in the third X buffer, the one the next tile's early copies leave alone
+    float *stg = (float *)(ring + 2 * HB + wave * (16 * EP4 * 4));
 
+    int m0, n0, n_end;
+    unsigned xo[8], wo[8];
+    // tile `t` of the panel walk: its origin, and this wave's copy offsets (every wave copies 64 rows of each
+    // operand tile per slab, 8 rows = 1 KB per instruction; lane l fills 16-byte slot l: row l>>3, physical
+    // k-chunk l&7 holding logical chunk (l&7) ^ (l>>3))
+#define G4_TILE(t)                                                                                     \
+    {                                                                                                  \
+        constexpr int PANEL = 4;                                                                       \
+        const int pidx = (t) / (PANEL * tiles_n), prem = (t) - pidx * (PANEL * tiles_n);               \
+        const int prow = min(PANEL, tiles_m - pidx * PANEL);                                           \
+        const int tn = prem / prow, tm = pidx * PANEL + prem - tn * prow;                              \
+        const int seg = tn / tiles_n_seg, tns = tn % tiles_n_seg;                                      \
+        n0 = seg * a.seg_n + tns * BN;                                                                 \
+        n_end = (seg + 1) * a.seg_n;                                                                   \
+        m0 = tm * BM;                                                                                  \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) {                                                \
+            const int row = min(m0 + wave * 64 + p * 8 + lrow, a.M - 1);                               \
+            const int n = min(n0 + wave * 64 + p * 8 + lrow, n_end - 1);                               \
+            xo[p] = ((unsigned)row * (unsigned)a.ldx + lch * 8) * 2u;                                  \
+            wo[p] = ((unsigned)n * (unsigned)a.ldw + lch * 8) * 2u;                                    \
+        }                                                                                              \
+    }
 #define G4_COPYX(k0, ldsb, p) glds_soff(Xb + (size_t)(k0) * 2, xo[p], ringa + (ldsb) + (p) * 1024);
 #define G4_COPYW(k0, ldsb, p) glds_soff(Wb + (size_t)(k0) * 2, wo[p], ringa + (ldsb) + (p) * 1024);
-#define G4_LDA(i, xs, k2) fa[i] = *(const bf16x8 *)(ring + (xs) + a_row + (i) * 16 * ROWB + ((((k2) * 4 + kg) ^ sw) << 4));
-#define G4_LDB(nb_, j, ws, k2) fb[nb_][j] = *(const bf16x8 *)(ring + (ws) + b_row + (j) * 16 * ROWB + ((((k2) * 4 + kg) ^ sw) << 4));
+    // the first copies of a tile.  Copies past the last slab repeat it (in bounds, never read), so the in-order
+    // copy counter can be waited on with the same constants from the first slab to the last.
+#define G4_HEAD4                                                                                       \
+    {                                                                                                  \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYW(0, 3 * HB, p)                           \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYX(0, 0, p)                                \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYW(k1, 4 * HB, p)                          \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYX(k1, HB, p)                              \
+    }
+#define G4_HEAD5 { _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYX(k2, 2 * HB, p) }
+#define G4_LDA(i, xs, k2_) fa[i] = *(const bf16x8 *)(ring + (xs) + a_row + (i) * 16 * ROWB + ((((k2_) * 4 + kg) ^ sw) << 4));
+#define G4_LDB(nb_, j, ws, k2_) fb[nb_][j] = *(const bf16x8 *)(ring + (ws) + b_row + (j) * 16 * ROWB + ((((k2_) * 4 + kg) ^ sw) << 4));
 #define G4_ROW(cb, i)                                                                                  \
     _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                      \
         asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fa[i]), "v"(fb[cb][j]));
     // one k-step: row i of MFMAs on fragment set cb, then the fragments of the next k-step that have
     // become free to load (A fragment i, B fragments 2i and 2i+1 of set nb_)
-#define G4_STEP(cb, nb_, xs, ws, k2)                                                                   \
+#define G4_STEP(cb, nb_, xs, ws, k2_)                                                                  \
     {                                                                                                  \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
             G4_ROW(cb, i)                                                                              \
-            if (i < 4) { G4_LDB(nb_, 2 * i, ws, k2) G4_LDB(nb_, 2 * i + 1, ws, k2) }                   \
-            G4_LDA(i, xs, k2)                                                                          \
+            if (i < 4) { G4_LDB(nb_, 2 * i, ws, k2_) G4_LDB(nb_, 2 * i + 1, ws, k2_) }                 \
+            G4_LDA(i, xs, k2_)                                                                         \
             __builtin_amdgcn_sched_barrier(0);                                                         \
         }                                                                                              \
     }
     // the same with this slab's copies: W of slab +2 (rows 0..3), then X of slab +3 (rows 4..7), into
     // the buffers the slab being finished has just released
-#define G4_STEPC(cb, nb_, xs, ws, k2, kw, kx)                                                          \
+#define G4_STEPC(cb, nb_, xs, ws, k2_, kw, kx)                                                         \
     {                                                                                                  \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
             G4_ROW(cb, i)                                                                              \
-            if (i < 4) { G4_LDB(nb_, 2 * i, ws, k2) G4_LDB(nb_, 2 * i + 1, ws, k2) }                   \
-            G4_LDA(i, xs, k2)                                                                          \
+            if (i < 4) { G4_LDB(nb_, 2 * i, ws, k2_) G4_LDB(nb_, 2 * i + 1, ws, k2_) }                 \
+            G4_LDA(i, xs, k2_)                                                                         \
             if (i < 4) { G4_COPYW(kw, wcur, 2 * i) G4_COPYW(kw, wcur, 2 * i + 1) }                     \
             else { G4_COPYX(kx, xcur, 2 * i - 8) G4_COPYX(kx, xcur, 2 * i - 7) }                       \
             __builtin_amdgcn_sched_barrier(0);                                                         \
         }                                                                                              \
     }
 
-    const int nk = a.K / BK, klast = (nk - 1) * BK;
-    int xcur = 0, wcur = 3 * HB;                         // buffers of the slab being computed
-    // copies past the last slab repeat it (in bounds, never read), so the in-order copy counter can
-    // be waited on with the same constants from the first slab to the last.  Queue: W0 X0 W1 X1 X2
-    {
-        const int k1 = min(BK, klast), k2 = min(2 * BK, klast);
-#pragma unroll
-        for (int p = 0; p < 8; ++p) G4_COPYW(0, 3 * HB, p)
-#pragma unroll
-        for (int p = 0; p < 8; ++p) G4_COPYX(0, 0, p)
-#pragma unroll
-        for (int p = 0; p < 8; ++p) G4_COPYW(k1, 4 * HB, p)
-#pragma unroll
-        for (int p = 0; p < 8; ++p) G4_COPYX(k1, HB, p)
-#pragma unroll
-        for (int p = 0; p < 8; ++p) G4_COPYX(k2, 2 * HB, p)
-    }
-    asm volatile("s_waitcnt vmcnt(24)" ::: "memory");    // W0, X0 have landed
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { G4_LDA(i, 0, 0) G4_LDB(0, i, 3 * HB, 0) }
-    for (int kt = 0;; ++kt) {                            // nk >= 1 (checked by the launcher)
-        const int xnxt = xcur == 2 * HB ? 0 : xcur + HB, wnxt = wcur ^ (3 * HB ^ 4 * HB);
-        G4_STEP(0, 1, xcur, wcur, 1)                     // MFMAs (slab kt, step 0); fetch (kt, step 1)
-        // slab kt+1 has landed (X of kt+2 may still be in flight); nobody reads slab kt's buffers any more
-        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+    G4_TILE(logical)
+    G4_HEAD4                                             // copy queue: W0 X0 W1 X1 ...
+    for (;;) {
+        G4_HEAD5                                         // ... X2
+        // Everything but X2 has landed: W0, X0 (and W1, X1, requested just before them or, from the second
+        // tile on, before the previous tile's epilogue).  The counter is in order, so this also waits for
+        // the previous tile's stores to be acknowledged, which they are within 0.2 us of being issued.
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         __syncthreads();
-        G4_STEPC(1, 0, xnxt, wnxt, 0, min((kt + 2) * BK, klast), min((kt + 3) * BK, klast))
-        xcur = xnxt; wcur = wnxt;
-        // The compiler takes an accumulator for finished where its MFMA is issued, and it moves accumulators
-        // between registers right where the loop ends.  The only way out of the loop is through these wait
-        // states, which let the last MFMAs retire first (a 16-pass result needs 19;
-        // tests/test_kernel_isa.py follows every path from the last MFMA in the compiled code).
-        if (kt + 1 >= nk) {
-            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-            break;
+        f32x4 acc[8][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
+        bf16x8 fa[8], fb[2][8];
+        int xcur = 0, wcur = 3 * HB;                     // buffers of the slab being computed
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { G4_LDA(i, 0, 0) G4_LDB(0, i, 3 * HB, 0) }
+        for (int kt = 0;; ++kt) {                        // nk >= 1 (checked by the launcher)
+            const int xnxt = xcur == 2 * HB ? 0 : xcur + HB, wnxt = wcur ^ (3 * HB ^ 4 * HB);
+            G4_STEP(0, 1, xcur, wcur, 1)                 // MFMAs (slab kt, step 0); fetch (kt, step 1)
+            // slab kt+1 has landed (X of kt+2 may still be in flight); nobody reads slab kt's buffers any more
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+            G4_STEPC(1, 0, xnxt, wnxt, 0, min((kt + 2) * BK, klast), min((kt + 3) * BK, klast))
+            xcur = xnxt; wcur = wnxt;
+            // The compiler takes an accumulator for finished where its MFMA is issued, and it moves
+            // accumulators between registers right where the loop ends.  The only way out of the loop is
+            // through these wait states, which let the last MFMAs retire first (a 16-pass result needs 19;
+            // tests/test_kernel_isa.py follows every path from the last MFMA in the compiled code).
+            if (kt + 1 >= nk) {
+                asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+                break;
+            }
         }
+        // all copies have landed and every wave is out of the loop before the ring is reused
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        // the next tile's first four half stages are requested now and arrive under this tile's epilogue
+        const int em0 = m0, en0 = n0, en_end = n_end;
+        const int next = logical + slots;
+        if (next < t_end) {
+            G4_TILE(next)
+            G4_HEAD4
+        }
+        if (em0 + BM <= a.M && en0 + BN <= en_end) epilogue4<EPI, true>(a, acc, stg, em0, en0, en_end, wm, wn, lane);
+        else epilogue4<EPI, false>(a, acc, stg, em0, en0, en_end, wm, wn, lane);
+        if (next >= t_end) break;
+        logical = next;
+        // the staging reads are done before the copy into the buffer they used is requested
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
     }
+#undef G4_TILE
+#undef G4_HEAD4
+#undef G4_HEAD5
 #undef G4_COPYX
 #undef G4_COPYW
 #undef G4_LDA
@@ -452,61 +543,6 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 #undef G4_ROW
 #undef G4_STEP
 #undef G4_STEPC
-    // all copies have landed and every wave is out of the loop before the ring is reused
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __syncthreads();
-    // ---- epilogue: as in the 8-wave kernel, 32 x 64 strips transposed through a private LDS strip;
-    //      a wave tile is 4 row strips x 2 column halves
-    constexpr int EP = 68;
-    float *stg = (float *)(ring + wave * (32 * EP * 4));
-    const int er = lane >> 3, ec = (lane & 7) * 8;
-    const int row_base = m0 + wm * 128 + er;
-#pragma unroll
-    for (int jh = 0; jh < 2; ++jh) {
-        const int gcol = n0 + wn * 128 + jh * 64 + ec;
-        float bias8[8];
-        {
-            bf16x8 b8;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) b8[i] = f2bf(0.f);
-            if (a.bias && gcol < n_end) b8 = *(const bf16x8 *)(a.bias + gcol);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) bias8[i] = bf2f(b8[i]);
-        }
-        AuxRow aux[2][4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int row = row_base + it * 8;
-            load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[0][it]);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (i + 1 < 4) {
-#pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    const int row = row_base + (i + 1) * 32 + it * 8;
-                    load_aux<EPI>(a, row, gcol, row < a.M && gcol < n_end, aux[(i + 1) & 1][it]);
-                }
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        stg[(h * 16 + 4 * kg + e) * EP + j * 16 + r16] = acc[2 * i + h][jh * 4 + j][e];
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int rl = it * 8 + er;
-                const float4 p0 = *(const float4 *)(stg + rl * EP + ec);
-                const float4 p1 = *(const float4 *)(stg + rl * EP + ec + 4);
-                float v[8] = {p0.x + bias8[0], p0.y + bias8[1], p0.z + bias8[2], p0.w + bias8[3],
-                              p1.x + bias8[4], p1.y + bias8[5], p1.z + bias8[6], p1.w + bias8[7]};
-                const int row = m0 + wm * 128 + i * 32 + rl;
-                if (row < a.M && gcol < n_end) store_row8<EPI>(a, row, gcol, v, aux[i & 1][it]);
-            }
-        }
-    }
 }
 
 template <int EPI>
@@ -515,7 +551,7 @@ int launch_t4(const GemmArgs &a, hipStream_t st)
     const int tiles_n = ((a.seg_n + BN - 1) / BN) * a.nseg;
     const int tiles_m = (a.M + BM - 1) / BM;
     const int nb = tiles_m * tiles_n;
-    const int grid = ((nb + 7) / 8) * 8;
+    const int grid = std::min(((nb + 7) / 8) * 8, 256);    // one block per CU, each walks its tiles
     hipLaunchKernelGGL((gemm_kernel4<EPI>), dim3(grid), dim3(NTHR4), 0, st, a);
     SL_CHECK_LAUNCH("gemm");
     return 0;
@@ -537,12 +573,7 @@ template <int EPI>
 int launch_e(const GemmArgs &a, int nz, hipStream_t st)
 {
     switch (nz) {
-    case 0:
-        // the GELU epilogues are ALU-bound and run better with two waves per SIMD to hide their latencies
-        // (measured at N = 4d, K = d: 8-wave 295 / 288 us, 4-wave 308 / 292 us); everything else gains
-        // 10-20 % from the 4-wave main loop
-        if (EPI == EPI_GELU || EPI == EPI_DGELU) return launch_t<EPI, 0>(a, st);
-        return launch_t4<EPI>(a, st);
+    case 0: return launch_t4<EPI>(a, st);                // no rank-space branch: the 4-wave kernel
     case 16: return launch_t<EPI, 16>(a, st);
     case 32: return launch_t<EPI, 32>(a, st);
     case 48: return launch_t<EPI, 48>(a, st);
