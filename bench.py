@@ -361,6 +361,7 @@ def main():
     torch.cuda.synchronize()
     el = time.perf_counter() - t0
     gemm_ms, gemm_flop, launches = B.slora_prof_read()
+    clock_mhz, clock_samples = B.slora_prof_read_clock()
     B.slora_prof_enable(0)
     hbm_kernels = attn_kernels = None
     if not args.no_legs:
@@ -498,6 +499,11 @@ def main():
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": recorded_gemm_traffic(),
                      "launches_timed": launches, "avg_launch_ms": gemm_ms / max(launches, 1),
+                     # the clock the chip held under this load (the datasheet peak is at 2400 MHz), from the
+                     # shader-clock and reference counters read by the 4-wave GEMM launches themselves
+                     "shader_clock_mhz": clock_mhz, "clock_samples": clock_samples,
+                     "frac_of_peak_at_observed_clock": (achieved / (PEAK_BF16_TFLOPS * clock_mhz / 2400.0)
+                                                        if clock_mhz > 0 else None),
                      "gemm_share_of_step": gemm_ms / max(launches, 1) * (launches / args.steps) / ms},
     }
     if hbm_kernels is not None:

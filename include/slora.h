@@ -320,6 +320,12 @@ enum { SLORA_PROF_GEMM = 0,      /* frozen products with the fused low-rank bran
 int slora_prof_enable(int kinds);
 int slora_prof_read_kind(int kind, double *h_ms, double *h_work, int *h_launches);
 int slora_prof_read(double *h_gemm_ms, double *h_gemm_flop, int *h_launches);
+/* The shader clock the chip held during the recorded GEMM launches, in MHz (the datasheet peak assumes 2400):
+ * while SLORA_PROF_GEMM is selected, the launches that run the 4-wave kernel store the shader-clock counter and
+ * the 100 MHz reference counter at their start and end; this call synchronises the device (it BLOCKS), and
+ * returns sum of shader ticks / sum of reference ticks x 100 over those launches and their number (0 MHz with no
+ * sample).  Uses 512 KB of device memory of the library's own (a static array). */
+int slora_prof_read_clock(double *h_mhz, int *h_samples);
 
 const char *slora_strerror(int code);
 const char *slora_last_hip_error(void);   /* text of the last failed HIP call on this thread */

@@ -32,7 +32,7 @@ EXPORTS = ["slora_create", "slora_destroy", "slora_workspace_bytes", "slora_bind
            "slora_frozen_linear_mxfp8", "slora_mx_weight_bytes", "slora_mx_pack_weight",
            "slora_mx_lora_linear_ws_bytes", "slora_mx_lora_linear_fwd", "slora_mx_lora_linear_bwd",
            "slora_server_fwd_mx", "slora_server_bwd_mx", "slora_mx_quantize_fp4",
-           "slora_frozen_linear_mxfp8_w4", "slora_lora_linear_bwd_noalloc", "slora_prof_read_kind"]
+           "slora_frozen_linear_mxfp8_w4", "slora_lora_linear_bwd_noalloc", "slora_prof_read_kind", "slora_prof_read_clock"]
 NOALLOC_SCRATCH_BYTES = 32 << 20
 (PROF_GEMM, PROF_LN_FWD, PROF_LN_BWD, PROF_LORA_GRAD, PROF_SGD, PROF_ATTN_FWD, PROF_ATTN_BWD, PROF_FEDAVG,
  PROF_KINDS) = range(9)
@@ -105,6 +105,7 @@ def lib():
         L.slora_prof_enable.argtypes = [i32]
         L.slora_prof_read.argtypes = [vp, vp, vp]
         L.slora_prof_read_kind.argtypes = [i32, vp, vp, vp]
+        L.slora_prof_read_clock.argtypes = [vp, vp]
         L.slora_strerror.argtypes = [i32]
         L.slora_strerror.restype = ctypes.c_char_p
         L.slora_last_hip_error.restype = ctypes.c_char_p
@@ -309,6 +310,13 @@ def slora_prof_read():
     ms, fl, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
     _check(lib().slora_prof_read(ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(n)))
     return ms.value, fl.value, n.value
+
+
+def slora_prof_read_clock():
+    """(shader clock in MHz during the recorded GEMM launches, number of launches sampled); blocks."""
+    mhz, n = ctypes.c_double(), ctypes.c_int()
+    _check(lib().slora_prof_read_clock(ctypes.byref(mhz), ctypes.byref(n)))
+    return mhz.value, n.value
 
 
 def slora_prof_read_kind(kind):

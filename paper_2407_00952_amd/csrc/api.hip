@@ -404,6 +404,11 @@ int slora_prof_read_kind(int kind, double *h_ms, double *h_work, int *h_launches
     return prof_read(kind, h_ms, h_work, h_launches) ? SLORA_EHIP : SLORA_OK;
 }
 
+int slora_prof_read_clock(double *h_mhz, int *h_samples)
+{
+    return prof_read_clock(h_mhz, h_samples) ? SLORA_EHIP : SLORA_OK;
+}
+
 int slora_prof_read(double *h_gemm_ms, double *h_gemm_flop, int *h_launches)
 {
     return slora_prof_read_kind(SLORA_PROF_GEMM, h_gemm_ms, h_gemm_flop, h_launches);

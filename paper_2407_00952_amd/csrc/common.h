@@ -94,6 +94,7 @@ struct GemmArgs {
     // codes [M,ldo] + scales [M,ldo/32], so that the product that consumes it needs no conversion pass
     unsigned char *oq, *os;
     static constexpr bool kEmitCodes = false;   // the bf16 kernel never does
+    unsigned long long *clk;         // measurement hook: four words for clock stamps of this launch, or null
 };
 
 int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);

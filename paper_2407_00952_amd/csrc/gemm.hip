@@ -404,6 +404,12 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int t_end = min(((int)(blockIdx.x & 7) + 1) * per_xcd, nb);
     int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= t_end) return;
+    // measurement hook: block 0 owns its CU from the first tile to the last, so the shader-clock and the
+    // 100 MHz reference counter at its start and end give the clock the chip held under this launch
+    if (a.clk != nullptr && blockIdx.x == 0 && tid == 0) {
+        a.clk[0] = __builtin_amdgcn_s_memtime();
+        a.clk[1] = __builtin_amdgcn_s_memrealtime();
+    }
     const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
     const char *Xb = (const char *)a.X, *Wb = (const char *)a.W;
     const unsigned ringa = lds_addr(ring) + wave * 64 * ROWB;
@@ -533,6 +539,10 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __syncthreads();
     }
+    if (a.clk != nullptr && blockIdx.x == 0 && tid == 0) {
+        a.clk[2] = __builtin_amdgcn_s_memtime();
+        a.clk[3] = __builtin_amdgcn_s_memrealtime();
+    }
 #undef G4_TILE
 #undef G4_HEAD4
 #undef G4_HEAD5
@@ -588,7 +598,9 @@ static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
 int launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st)
 {
     const bool rec = prof_begin(PK_GEMM, st);
-    const int rc = launch_gemm_inner(a, epi, nz, st);
+    GemmArgs b = a;
+    b.clk = prof_clock_words(rec);
+    const int rc = launch_gemm_inner(b, epi, nz, st);
     // algorithmic work of this launch: the frozen product only (the rank-r branch adds < 1 % and is left
     // out, which understates the achieved rate slightly)
     prof_end(rec, PK_GEMM, 2.0 * a.M * (double)a.N * a.K, st);
