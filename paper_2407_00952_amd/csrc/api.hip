@@ -205,7 +205,12 @@ void plan_workspace(slora_ctx *c)
     c->t_du = take(2 * T * d);
     c->t_ps = take(2 * T * 64);
     c->t_delta = take(4 * T * H);
-    c->t_part = take(4 * lora_grad_partial_floats(c->maxT, (int)(dff > d ? dff : d)));
+    // adapter-gradient partial sums: the five jobs of the q|k|v group (width d each), or the dA + dB pair of
+    // one of the other projections (widths d and d_ff at most)
+    {
+        const size_t fd = lora_grad_partial_floats(c->maxT, (int)d), ff = lora_grad_partial_floats(c->maxT, (int)dff);
+        c->t_part = take(4 * (5 * fd > fd + ff ? 5 * fd : fd + ff));
+    }
     c->t_xq = c->t_xs = c->t_qa = c->t_qas = c->t_qb = c->t_qbs = 0;
     if (c->mx) {
         const size_t kmax = dff > 3 * d ? dff : 3 * d;
@@ -366,10 +371,12 @@ int lora_grads(slora_ctx *c, int l, int p, const bf16 *x, int ldx, const bf16 *d
     proj_shape(c, p, n_in, n_out);
     const AdapterBind &ab = c->adapters[l][p];
     float *part = at<float>(c, c->t_part);
-    // dA [r,in] = ps^T x
-    if ((rc = launch_lora_grad(x, ldx, n_in, ps, ldps, c->r, c->T, part, ab.dA, 1, st))) return rc;
-    // dB [out,r] = dy^T zs
-    return launch_lora_grad(dy, ldy_, n_out, at<bf16>(c, c->bw[l].zs[p]), SL_RP, c->r, c->T, part, ab.dB, 0, st);
+    // dA [r,in] = ps^T x and dB [out,r] = dy^T zs, one launch for the two
+    const LoraGradDesc jobs[2] = {
+        {x, ps, part, ab.dA, nullptr, ldx, ldps, n_in, false, 1},
+        {dy, at<bf16>(c, c->bw[l].zs[p]), part + lora_grad_partial_floats(c->maxT, n_in), ab.dB, nullptr, ldy_, SL_RP, n_out,
+         false, 0}};
+    return launch_lora_grad_jobs(jobs, 2, c->r, c->T, st);
 }
 
 }  // namespace
@@ -740,27 +747,28 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
             set_mx(c, l, MXW_QKVT, a, mxo);
             if ((rc = launch_gemm(a, EPI_STORE, c->n_qkv ? c->nz_qkv : 0, st))) return rc;
             // dB per adapted projection (its own slice of dq|dk|dv against its own zs); dA for the adapters
-            // two at a time: they share the operand u, and their rank-space gradients sit side by side in ps
-            float *part = at<float>(c, c->t_part);
-            int slot_proj[3], nslot = 0;
-            for (int p = 0; p < 3; ++p)
-                if (adapted(c, p)) {
-                    slot_proj[c->qkv_idx[p]] = p;
-                    ++nslot;
-                    if ((rc = launch_lora_grad(dqkv + (size_t)p * d, 3 * d, d, at<bf16>(c, b.zs[p]), SL_RP, c->r, T, part,
-                                               c->adapters[l][p].dB, 0, st)))
-                        return rc;
+            // two at a time: they share the operand u, and their rank-space gradients sit side by side in ps.
+            // All of them go out as one launch (each with partial-sum scratch of its own).
+            if (c->n_qkv) {
+                const size_t part_stride = lora_grad_partial_floats(c->maxT, d);
+                float *part = at<float>(c, c->t_part);
+                LoraGradDesc jobs[5];
+                int nj = 0, slot_proj[3], nslot = 0;
+                for (int p = 0; p < 3; ++p)
+                    if (adapted(c, p)) {
+                        slot_proj[c->qkv_idx[p]] = p;
+                        ++nslot;
+                        jobs[nj] = {dqkv + (size_t)p * d, at<bf16>(c, b.zs[p]), part + nj * part_stride,
+                                    c->adapters[l][p].dB, nullptr, 3 * d, SL_RP, d, false, 0};
+                        ++nj;
+                    }
+                for (int sl = 0; sl < nslot; sl += 2) {
+                    const bool pair = sl + 1 < nslot;
+                    jobs[nj] = {at<bf16>(c, b.u), ps + 16 * sl, part + nj * part_stride, c->adapters[l][slot_proj[sl]].dA,
+                                pair ? c->adapters[l][slot_proj[sl + 1]].dA : nullptr, d, c->k2_qkv, d, pair, 1};
+                    ++nj;
                 }
-            for (int sl = 0; sl < nslot; sl += 2) {
-                const bf16 *ys = ps + 16 * sl;
-                if (sl + 1 < nslot)
-                    rc = launch_lora_grad_pair(at<bf16>(c, b.u), d, d, ys, c->k2_qkv, c->r, T, part,
-                                               c->adapters[l][slot_proj[sl]].dA, c->adapters[l][slot_proj[sl + 1]].dA, 1,
-                                               st);
-                else
-                    rc = launch_lora_grad(at<bf16>(c, b.u), d, d, ys, c->k2_qkv, c->r, T, part,
-                                          c->adapters[l][slot_proj[sl]].dA, 1, st);
-                if (rc) return rc;
+                if ((rc = launch_lora_grad_jobs(jobs, nj, c->r, T, st))) return rc;
             }
         }
         // dh = dh' + LN1^T(du): next block's incoming gradient, or the clients' activation gradients

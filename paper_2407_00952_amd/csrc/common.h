@@ -122,6 +122,14 @@ int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int 
 int launch_lora_grad_pair(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T,
                           float *partials, float *out_a, float *out_b, int out_is_rxC, hipStream_t st);
 size_t lora_grad_partial_floats(int T, int C);
+// several of them in one launch pair (same T and r; each with partial-sum scratch of its own)
+struct LoraGradDesc {
+    const bf16 *X; const bf16 *Y;    // tall operand [T,C] (pitch ldx); skinny operand [T,16] (or [T,32] when dual)
+    float *partials;                 // lora_grad_partial_floats(T, C) floats
+    float *out_a, *out_b;            // out_b: the second adapter of a dual job, else null
+    int ldx, ldy, C; bool dual; int out_is_rxC;
+};
+int launch_lora_grad_jobs(const LoraGradDesc *d, int njobs, int r, int T, hipStream_t st);
 int launch_fedavg(int K, const float *const *x, const float *w, size_t n, float *out, hipStream_t st);
 int launch_sgd(float *p, const float *g, float lr, size_t n, hipStream_t st);
 int launch_adamw(float *p, const float *g, float *m, float *v, size_t n, float b1, float b2, float eps, float decay,

@@ -62,13 +62,12 @@ __device__ __forceinline__ bf16x8 yfrag_tr(const unsigned char *t, int tok0, int
 // DUAL: Y holds two adapters' rank-space columns side by side (16 + 16); their partial results are
 // stored one after the other (rows 0..r-1 and r..2r-1 of the chunk), so X is streamed once for both.
 template <bool DUAL>
-__global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__restrict__ X, int ldx, int C,
-                                                                const bf16 *__restrict__ Y, int ldy, int r, int T,
-                                                                float *__restrict__ partials)
+__device__ __forceinline__ void lora_grad_partial_body(const bf16 *__restrict__ X, int ldx, int C,
+                                                       const bf16 *__restrict__ Y, int ldy, int r, int T,
+                                                       float *__restrict__ partials, unsigned char *X0,
+                                                       unsigned char *X1, unsigned char *Y0, unsigned char *Y1)
 {
     constexpr int YP = DUAL ? 96 : 32;
-    __shared__ __attribute__((aligned(1024))) unsigned char X0[GX_TILE], X1[GX_TILE];
-    __shared__ __attribute__((aligned(16))) unsigned char Y0[64 * YP], Y1[64 * YP];
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c_blk = blockIdx.x * GR_COLS;
@@ -155,14 +154,41 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const bf16 *__re
     }
 }
 
+// One launch for every adapter gradient that is due at one point of the backward pass (after the fused
+// q|k|v input-gradient product: dB of each adapted projection and dA of all of them): blockIdx.z picks the
+// job.  The jobs are a few dozen microseconds of streaming each, so launching them one by one (and their
+// reductions one by one) left the chip half idle between them.
+struct LoraGradJob {
+    const bf16 *X; const bf16 *Y;    // tall operand [T,C] (pitch ldx), skinny operand [T,16 or 32] (pitch ldy)
+    float *partials;                 // this job's chunk partial sums
+    float *out_a, *out_b;            // result(s); out_b only for a dual job
+    int ldx, ldy, C, dual, out_is_rxC;
+};
+constexpr int LG_MAX_JOBS = 6;
+struct LoraGradJobs { LoraGradJob j[LG_MAX_JOBS]; };
+
+__global__ __launch_bounds__(256) void lora_grad_partial_kernel(LoraGradJobs jobs, int r, int T)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char X0[GX_TILE], X1[GX_TILE];
+    __shared__ __attribute__((aligned(16))) unsigned char Y0[64 * 96], Y1[64 * 96];
+    const LoraGradJob &jb = jobs.j[blockIdx.z];
+    if ((int)blockIdx.x * GR_COLS >= jb.C) return;       // this job's operand is narrower than the widest one
+    if (jb.dual) lora_grad_partial_body<true>(jb.X, jb.ldx, jb.C, jb.Y, jb.ldy, r, T, jb.partials, X0, X1, Y0, Y1);
+    else lora_grad_partial_body<false>(jb.X, jb.ldx, jb.C, jb.Y, jb.ldy, r, T, jb.partials, X0, X1, Y0, Y1);
+}
+
 // out[j, c] = sum over chunks, in a fixed order: each of the 4 wavefronts of a block sums a
 // contiguous quarter of the chunks in increasing order, then the four are added in order.
 // With a second output, rows r..2r-1 of every chunk belong to it (two adapters reduced in one launch).
-__global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float *__restrict__ partials, int nchunk, int r,
-                                                               int C, float *__restrict__ out,
-                                                               float *__restrict__ out_second, int out_is_rxC)
+__global__ __launch_bounds__(256) void lora_grad_reduce_kernel(LoraGradJobs jobs, int nchunk, int r)
 {
     __shared__ float red[3][64];
+    const LoraGradJob &jb = jobs.j[blockIdx.z];
+    const float *__restrict__ partials = jb.partials;
+    const int C = jb.C, out_is_rxC = jb.out_is_rxC;
+    float *__restrict__ out = jb.out_a;
+    float *__restrict__ out_second = jb.dual ? jb.out_b : nullptr;
+    if ((int)blockIdx.x * 64 >= (jb.dual ? 2 * r : r) * C) return;      // (uniform: before the barrier)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nrows = out_second ? 2 * r : r;
     const int idx = blockIdx.x * 64 + lane;              // over nrows*C, c fastest
@@ -323,39 +349,46 @@ size_t lora_grad_partial_floats(int T, int C)
     return nchunk * 2 * SL_RP * (size_t)C;               // room for two adapters reduced together
 }
 
+int launch_lora_grad_jobs(const LoraGradDesc *d, int njobs, int r, int T, hipStream_t st)
+{
+    if (njobs < 1 || njobs > LG_MAX_JOBS || T <= 0 || r < 1 || r > 16) return SL_EINVAL;
+    LoraGradJobs jobs;
+    int max_c = 0, max_red = 0;
+    double bytes = 0.0;
+    for (int k = 0; k < njobs; ++k) {
+        const LoraGradDesc &q = d[k];
+        if (!q.X || !q.Y || !q.partials || !q.out_a || (q.dual && !q.out_b)) return SL_EINVAL;
+        if (q.C <= 0 || (q.C % 64) || (q.ldx % 8) || (q.ldy % 8) || (q.dual && q.ldy < 32)) return SL_EINVAL;
+        jobs.j[k] = {q.X, q.Y, q.partials, q.out_a, q.out_b, q.ldx, q.ldy, q.C, q.dual ? 1 : 0, q.out_is_rxC};
+        max_c = q.C > max_c ? q.C : max_c;
+        const int red = (q.dual ? 2 * r : r) * q.C;
+        max_red = red > max_red ? red : max_red;
+        bytes += 2.0 * T * (double)q.C;                  // the streaming pass: the tall operand once
+    }
+    const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
+    const bool rec = prof_begin(PK_LORA_GRAD, st);
+    hipLaunchKernelGGL(lora_grad_partial_kernel, dim3((max_c + GR_COLS - 1) / GR_COLS, nchunk, njobs), dim3(256), 0, st,
+                       jobs, r, T);
+    prof_end(rec, PK_LORA_GRAD, bytes, st);
+    SL_CHECK_LAUNCH("lora_grad_partial");
+    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((max_red + 63) / 64, 1, njobs), dim3(256), 0, st, jobs, nchunk, r);
+    SL_CHECK_LAUNCH("lora_grad_reduce");
+    return 0;
+}
+
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
                      float *out, int out_is_rxC, hipStream_t st)
 {
-    if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || r < 1 || r > 16) return SL_EINVAL;
-    const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
-    dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
-    // algorithmic bytes of the streaming pass: the tall operand once, the skinny one once per column block
-    const bool rec = prof_begin(PK_LORA_GRAD, st);
-    hipLaunchKernelGGL((lora_grad_partial_kernel<false>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
-    prof_end(rec, PK_LORA_GRAD, 2.0 * T * (double)C, st);
-    SL_CHECK_LAUNCH("lora_grad_partial");
-    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
-                       out, (float *)nullptr, out_is_rxC);
-    SL_CHECK_LAUNCH("lora_grad_reduce");
-    return 0;
+    const LoraGradDesc d = {X, Y, partials, out, nullptr, ldx, ldy, C, false, out_is_rxC};
+    return launch_lora_grad_jobs(&d, 1, r, T, st);
 }
 
 // Two adapters that share X: Y carries their rank-space columns in [0,16) and [16,32) of each row.
 int launch_lora_grad_pair(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T, float *partials,
                           float *out_a, float *out_b, int out_is_rxC, hipStream_t st)
 {
-    if (T <= 0 || C <= 0 || (C % 64) || (ldx % 8) || (ldy % 8) || ldy < 32 || r < 1 || r > 16 || !out_a || !out_b)
-        return SL_EINVAL;
-    const int nchunk = (T + GR_ROWS - 1) / GR_ROWS;
-    dim3 grid((C + GR_COLS - 1) / GR_COLS, nchunk);
-    const bool rec = prof_begin(PK_LORA_GRAD, st);
-    hipLaunchKernelGGL((lora_grad_partial_kernel<true>), grid, dim3(256), 0, st, X, ldx, C, Y, ldy, r, T, partials);
-    prof_end(rec, PK_LORA_GRAD, 2.0 * T * (double)C, st);
-    SL_CHECK_LAUNCH("lora_grad_partial");
-    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((2 * r * C + 63) / 64), dim3(256), 0, st, partials, nchunk, r, C,
-                       out_a, out_b, out_is_rxC);
-    SL_CHECK_LAUNCH("lora_grad_reduce");
-    return 0;
+    const LoraGradDesc d = {X, Y, partials, out_a, out_b, ldx, ldy, C, true, out_is_rxC};
+    return launch_lora_grad_jobs(&d, 1, r, T, st);
 }
 
 int launch_sgd(float *p, const float *g, float lr, size_t n, hipStream_t st)
