@@ -330,15 +330,16 @@ constexpr int EP4 = 68;                      // pitch (floats) of an epilogue st
 // the matrix: every tile at the model's shapes) has no branch at all, so the compiler waits for exactly the
 // loads a strip needs (partial vmcnt counts) instead of draining every load and store at each predicated
 // block; the operands that come from global memory are requested four strips ahead.
-template <int EPI, bool INTERIOR>
-__device__ __forceinline__ void epilogue4(const GemmArgs &a, f32x4 (&acc)[8][8], float *stg, int m0, int n0,
+template <int EPI, bool INTERIOR, int NI>
+__device__ __forceinline__ void epilogue4(const GemmArgs &a, f32x4 (&acc)[NI][8], float *stg, int m0, int n0,
                                           int n_end, int wm, int wn, int lane)
 {
+    constexpr int NS = 2 * NI;                           // strips: NI row strips x 2 column halves
     const int r16 = lane & 15, kg = lane >> 4;
     const int er = lane >> 3, ec = (lane & 7) * 8;
-    const int row_base = m0 + wm * 128 + er;
+    const int row_base = m0 + wm * (16 * NI) + er;
     constexpr int AHEAD = 4;
-    AuxRow aux[16][2];
+    AuxRow aux[NS][2];
     float bias8[2][8];
 #pragma unroll
     for (int jh = 0; jh < 2; ++jh) {
@@ -352,15 +353,15 @@ __device__ __forceinline__ void epilogue4(const GemmArgs &a, f32x4 (&acc)[8][8],
     }
 #define E4_AUX(s_)                                                                                     \
     _Pragma("unroll") for (int it = 0; it < 2; ++it) {                                                 \
-        const int row_ = row_base + ((s_) & 7) * 16 + it * 8, col_ = n0 + wn * 128 + ((s_) >> 3) * 64 + ec; \
+        const int row_ = row_base + ((s_) % NI) * 16 + it * 8, col_ = n0 + wn * 128 + ((s_) / NI) * 64 + ec; \
         load_aux<EPI>(a, row_, col_, INTERIOR || (row_ < a.M && col_ < n_end), aux[s_][it]);           \
     }
 #pragma unroll
     for (int s = 0; s < AHEAD; ++s) E4_AUX(s)
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {                       // strip s: column half s >> 3, rows 16 (s & 7) ..
-        const int jh = s >> 3, i = s & 7;
-        if (s + AHEAD < 16) E4_AUX(s + AHEAD)
+    for (int s = 0; s < NS; ++s) {                       // strip s: column half s / NI, rows 16 (s % NI) ..
+        const int jh = s / NI, i = s % NI;
+        if (s + AHEAD < NS) E4_AUX(s + AHEAD)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -372,16 +373,19 @@ __device__ __forceinline__ void epilogue4(const GemmArgs &a, f32x4 (&acc)[8][8],
             const float4 p1 = *(const float4 *)(stg + rl * EP4 + ec + 4);
             float v[8] = {p0.x + bias8[jh][0], p0.y + bias8[jh][1], p0.z + bias8[jh][2], p0.w + bias8[jh][3],
                           p1.x + bias8[jh][4], p1.y + bias8[jh][5], p1.z + bias8[jh][6], p1.w + bias8[jh][7]};
-            const int row = m0 + wm * 128 + i * 16 + rl, gcol = n0 + wn * 128 + jh * 64 + ec;
+            const int row = m0 + wm * (16 * NI) + i * 16 + rl, gcol = n0 + wn * 128 + jh * 64 + ec;
             if (INTERIOR || (row < a.M && gcol < n_end)) store_row8<EPI>(a, row, gcol, v, aux[s][it]);
         }
     }
 #undef E4_AUX
 }
 
-template <int EPI>
+// NI = 16-row MFMA tiles per wave along M: 8 (tile 256 x 256, wave tile 128 x 128) or 4 (tile 128 x 256, wave
+// tile 64 x 128) for launches that have fewer 256-row tiles than the chip has CUs.
+template <int EPI, int NI>
 __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel4(GemmArgs a)
 {
+    constexpr int BM4 = 32 * NI;                         // rows of a block tile
     __shared__ __attribute__((aligned(1024))) unsigned char ring[5 * HB];   // X: 0, HB, 2HB;  W: 3HB, 4HB
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -397,7 +401,7 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     // the current one (2.5 us per tile otherwise, a tenth of a K = 1024 tile).
     const int tiles_n_seg = (a.seg_n + BN - 1) / BN;
     const int tiles_n = tiles_n_seg * a.nseg;
-    const int tiles_m = (a.M + BM - 1) / BM;
+    const int tiles_m = (a.M + BM4 - 1) / BM4;
     const int nb = tiles_m * tiles_n;
     const int per_xcd = (nb + 7) >> 3;
     const int slots = gridDim.x >> 3;
@@ -412,8 +416,8 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     }
     const int lrow = lane >> 3, lch = (lane & 7) ^ (lane >> 3);
     const char *Xb = (const char *)a.X, *Wb = (const char *)a.W;
-    const unsigned ringa = lds_addr(ring) + wave * 64 * ROWB;
-    const int a_row = (wm * 128 + r16) * ROWB, b_row = (wn * 128 + r16) * ROWB;
+    const unsigned ringa_x = lds_addr(ring) + wave * (8 * NI) * ROWB, ringa_w = lds_addr(ring) + wave * 64 * ROWB;
+    const int a_row = (wm * (16 * NI) + r16) * ROWB, b_row = (wn * 128 + r16) * ROWB;
     const int sw = r16 & 7;
     const int nk = a.K / BK, klast = (nk - 1) * BK;
     const int k1 = min(BK, klast), k2 = min(2 * BK, klast);
@@ -422,9 +426,9 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 
     int m0, n0, n_end;
     unsigned xo[8], wo[8];
-    // tile `t` of the panel walk: its origin, and this wave's copy offsets (every wave copies 64 rows of each
-    // operand tile per slab, 8 rows = 1 KB per instruction; lane l fills 16-byte slot l: row l>>3, physical
-    // k-chunk l&7 holding logical chunk (l&7) ^ (l>>3))
+    // tile `t` of the panel walk: its origin, and this wave's copy offsets (every wave copies a quarter of the
+    // rows of each operand tile per slab -- 8 NI of X, 64 of W --, 8 rows = 1 KB per instruction; lane l fills
+    // 16-byte slot l: row l>>3, physical k-chunk l&7 holding logical chunk (l&7) ^ (l>>3))
 #define G4_TILE(t)                                                                                     \
     {                                                                                                  \
         constexpr int PANEL = 4;                                                                       \
@@ -434,26 +438,26 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         const int seg = tn / tiles_n_seg, tns = tn % tiles_n_seg;                                      \
         n0 = seg * a.seg_n + tns * BN;                                                                 \
         n_end = (seg + 1) * a.seg_n;                                                                   \
-        m0 = tm * BM;                                                                                  \
+        m0 = tm * BM4;                                                                                 \
         _Pragma("unroll") for (int p = 0; p < 8; ++p) {                                                \
-            const int row = min(m0 + wave * 64 + p * 8 + lrow, a.M - 1);                               \
+            const int row = min(m0 + wave * (8 * NI) + (p % NI) * 8 + lrow, a.M - 1);                  \
             const int n = min(n0 + wave * 64 + p * 8 + lrow, n_end - 1);                               \
             xo[p] = ((unsigned)row * (unsigned)a.ldx + lch * 8) * 2u;                                  \
             wo[p] = ((unsigned)n * (unsigned)a.ldw + lch * 8) * 2u;                                    \
         }                                                                                              \
     }
-#define G4_COPYX(k0, ldsb, p) glds_soff(Xb + (size_t)(k0) * 2, xo[p], ringa + (ldsb) + (p) * 1024);
-#define G4_COPYW(k0, ldsb, p) glds_soff(Wb + (size_t)(k0) * 2, wo[p], ringa + (ldsb) + (p) * 1024);
+#define G4_COPYX(k0, ldsb, p) glds_soff(Xb + (size_t)(k0) * 2, xo[p], ringa_x + (ldsb) + (p) * 1024);
+#define G4_COPYW(k0, ldsb, p) glds_soff(Wb + (size_t)(k0) * 2, wo[p], ringa_w + (ldsb) + (p) * 1024);
     // the first copies of a tile.  Copies past the last slab repeat it (in bounds, never read), so the in-order
     // copy counter can be waited on with the same constants from the first slab to the last.
 #define G4_HEAD4                                                                                       \
     {                                                                                                  \
         _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYW(0, 3 * HB, p)                           \
-        _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYX(0, 0, p)                                \
+        _Pragma("unroll") for (int p = 0; p < NI; ++p) G4_COPYX(0, 0, p)                               \
         _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYW(k1, 4 * HB, p)                          \
-        _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYX(k1, HB, p)                              \
+        _Pragma("unroll") for (int p = 0; p < NI; ++p) G4_COPYX(k1, HB, p)                             \
     }
-#define G4_HEAD5 { _Pragma("unroll") for (int p = 0; p < 8; ++p) G4_COPYX(k2, 2 * HB, p) }
+#define G4_HEAD5 { _Pragma("unroll") for (int p = 0; p < NI; ++p) G4_COPYX(k2, 2 * HB, p) }
 #define G4_LDA(i, xs, k2_) fa[i] = *(const bf16x8 *)(ring + (xs) + a_row + (i) * 16 * ROWB + ((((k2_) * 4 + kg) ^ sw) << 4));
 #define G4_LDB(nb_, j, ws, k2_) fb[nb_][j] = *(const bf16x8 *)(ring + (ws) + b_row + (j) * 16 * ROWB + ((((k2_) * 4 + kg) ^ sw) << 4));
 #define G4_ROW(cb, i)                                                                                  \
@@ -463,23 +467,27 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     // become free to load (A fragment i, B fragments 2i and 2i+1 of set nb_)
 #define G4_STEP(cb, nb_, xs, ws, k2_)                                                                  \
     {                                                                                                  \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
+        _Pragma("unroll") for (int i = 0; i < NI; ++i) {                                               \
             G4_ROW(cb, i)                                                                              \
             if (i < 4) { G4_LDB(nb_, 2 * i, ws, k2_) G4_LDB(nb_, 2 * i + 1, ws, k2_) }                 \
             G4_LDA(i, xs, k2_)                                                                         \
             __builtin_amdgcn_sched_barrier(0);                                                         \
         }                                                                                              \
     }
-    // the same with this slab's copies: W of slab +2 (rows 0..3), then X of slab +3 (rows 4..7), into
-    // the buffers the slab being finished has just released
+    // the same with this slab's copies: W of slab +2 (rows 0..3), then X of slab +3 (rows 4..7; with four rows
+    // all of them behind the last W copy), into the buffers the slab being finished has just released.  The X
+    // copies must be the LAST ones issued: the wait in front of the barrier lets exactly NI copies stay in
+    // flight, and those must be X of slab +3, never W of slab +2
 #define G4_STEPC(cb, nb_, xs, ws, k2_, kw, kx)                                                         \
     {                                                                                                  \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
+        _Pragma("unroll") for (int i = 0; i < NI; ++i) {                                               \
             G4_ROW(cb, i)                                                                              \
             if (i < 4) { G4_LDB(nb_, 2 * i, ws, k2_) G4_LDB(nb_, 2 * i + 1, ws, k2_) }                 \
             G4_LDA(i, xs, k2_)                                                                         \
             if (i < 4) { G4_COPYW(kw, wcur, 2 * i) G4_COPYW(kw, wcur, 2 * i + 1) }                     \
-            else { G4_COPYX(kx, xcur, 2 * i - 8) G4_COPYX(kx, xcur, 2 * i - 7) }                       \
+            if (NI == 8 && i >= 4) { G4_COPYX(kx, xcur, 2 * i - 8) G4_COPYX(kx, xcur, 2 * i - 7) }     \
+            if (NI == 4 && i == 3) { G4_COPYX(kx, xcur, 0) G4_COPYX(kx, xcur, 1)                       \
+                                     G4_COPYX(kx, xcur, 2) G4_COPYX(kx, xcur, 3) }                     \
             __builtin_amdgcn_sched_barrier(0);                                                         \
         }                                                                                              \
     }
@@ -488,27 +496,27 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     G4_HEAD4                                             // copy queue: W0 X0 W1 X1 ...
     for (;;) {
         G4_HEAD5                                         // ... X2
-        // Everything but X2 has landed: W0, X0 (and W1, X1, requested just before them or, from the second
+        // Everything but X2 (NI copies) has landed: W0, X0 (and W1, X1, requested just before them or, from the second
         // tile on, before the previous tile's epilogue).  The counter is in order, so this also waits for
         // the previous tile's stores to be acknowledged, which they are within 0.2 us of being issued.
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI) : "memory");
         __syncthreads();
-        f32x4 acc[8][8];
+        f32x4 acc[NI][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < 8; ++j)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
-        bf16x8 fa[8], fb[2][8];
+        bf16x8 fa[NI], fb[2][8];
         int xcur = 0, wcur = 3 * HB;                     // buffers of the slab being computed
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { G4_LDA(i, 0, 0) G4_LDB(0, i, 3 * HB, 0) }
+        for (int i = 0; i < 8; ++i) { if (i < NI) { G4_LDA(i, 0, 0) } G4_LDB(0, i, 3 * HB, 0) }
         for (int kt = 0;; ++kt) {                        // nk >= 1 (checked by the launcher)
             const int xnxt = xcur == 2 * HB ? 0 : xcur + HB, wnxt = wcur ^ (3 * HB ^ 4 * HB);
             G4_STEP(0, 1, xcur, wcur, 1)                 // MFMAs (slab kt, step 0); fetch (kt, step 1)
             // slab kt+1 has landed (X of kt+2 may still be in flight); nobody reads slab kt's buffers any more
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NI) : "memory");
             __syncthreads();
             G4_STEPC(1, 0, xnxt, wnxt, 0, min((kt + 2) * BK, klast), min((kt + 3) * BK, klast))
             xcur = xnxt; wcur = wnxt;
@@ -531,8 +539,8 @@ __global__ __launch_bounds__(NTHR4) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             G4_TILE(next)
             G4_HEAD4
         }
-        if (em0 + BM <= a.M && en0 + BN <= en_end) epilogue4<EPI, true>(a, acc, stg, em0, en0, en_end, wm, wn, lane);
-        else epilogue4<EPI, false>(a, acc, stg, em0, en0, en_end, wm, wn, lane);
+        if (em0 + BM4 <= a.M && en0 + BN <= en_end) epilogue4<EPI, true, NI>(a, acc, stg, em0, en0, en_end, wm, wn, lane);
+        else epilogue4<EPI, false, NI>(a, acc, stg, em0, en0, en_end, wm, wn, lane);
         if (next >= t_end) break;
         logical = next;
         // the staging reads are done before the copy into the buffer they used is requested
@@ -559,10 +567,15 @@ template <int EPI>
 int launch_t4(const GemmArgs &a, hipStream_t st)
 {
     const int tiles_n = ((a.seg_n + BN - 1) / BN) * a.nseg;
-    const int tiles_m = (a.M + BM - 1) / BM;
-    const int nb = tiles_m * tiles_n;
+    const int nb8 = ((a.M + 255) / 256) * tiles_n, nb4 = ((a.M + 127) / 128) * tiles_n;
+    // 128-row tiles where they fill the chip better: rounds of 256 tiles, a 128-row tile costing a good half of
+    // a 256-row one (e.g. the d x d products of a 10 240-token batch at d = 768: 120 tiles of 256 rows would leave
+    // half of the CUs idle); small problems stay on the 256-row tile, whichever way they fit
+    const bool half = a.M >= 1024 && 0.55 * ((nb4 + 255) / 256) < 1.0 * ((nb8 + 255) / 256);
+    const int nb = half ? nb4 : nb8;
     const int grid = std::min(((nb + 7) / 8) * 8, 256);    // one block per CU, each walks its tiles
-    hipLaunchKernelGGL((gemm_kernel4<EPI>), dim3(grid), dim3(NTHR4), 0, st, a);
+    if (half) hipLaunchKernelGGL((gemm_kernel4<EPI, 4>), dim3(grid), dim3(NTHR4), 0, st, a);
+    else hipLaunchKernelGGL((gemm_kernel4<EPI, 8>), dim3(grid), dim3(NTHR4), 0, st, a);
     SL_CHECK_LAUNCH("gemm");
     return 0;
 }

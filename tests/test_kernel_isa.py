@@ -93,11 +93,13 @@ def gemm_asm():
 
 def test_four_wave_gemm_mfma_hazards(gemm_asm):
     funcs = {n: b for n, b in _functions(gemm_asm).items() if "gemm_kernel4" in n}
-    assert len(funcs) == 4, sorted(funcs)          # one per epilogue
+    assert len(funcs) == 8, sorted(funcs)          # four epilogues x two tile heights
     for name, body in funcs.items():
+        ni = int(re.search(r"gemm_kernel4ILi\d+ELi(\d+)E", name).group(1))      # 16-row MFMA tiles per wave along M
+        assert ni in (4, 8), name
         mf = [(i, ins) for i, ins in enumerate(body) if ins.startswith("v_mfma")]
-        # the unrolled loop body: 2 k-steps x 64 MFMAs
-        assert len(mf) == 128, (name, len(mf))
+        # the unrolled loop body: 2 k-steps x (ni x 8) MFMAs
+        assert len(mf) == 2 * 8 * ni, (name, len(mf))
         ranges = []
         for _, ins in mf:
             m = re.match(r"v_mfma_f32_16x16x32_bf16 a\[(\d+):(\d+)\], v\[\d+:\d+\], v\[\d+:\d+\], a\[(\d+):(\d+)\]$", ins)
@@ -105,9 +107,10 @@ def test_four_wave_gemm_mfma_hazards(gemm_asm):
             d0, d1, c0, c1 = map(int, m.groups())
             assert (d0, d1) == (c0, c1) and d1 - d0 == 3 and d0 % 4 == 0, (name, ins)      # (1) in place, aligned
             ranges.append(d0)
-        # 64 distinct accumulators per k-step, the same 64 in both, covering all 256 registers: a register is
-        # written again 64 MFMAs later at the earliest and ranges never overlap partially
-        assert sorted(ranges[:64]) == sorted(ranges[64:]) == list(range(0, 256, 4)), name
+        # ni x 8 distinct accumulators per k-step, the same ones in both: a register is written again that many
+        # MFMAs later at the earliest and ranges never overlap partially
+        half = 8 * ni
+        assert sorted(ranges[:half]) == sorted(ranges[half:]) and len(set(ranges[:half])) == half, name
         first, last = mf[0][0], mf[-1][0]
         # (2) nothing else touches an accumulation register between the first and the last MFMA
         for ins in body[first:last + 1]:
