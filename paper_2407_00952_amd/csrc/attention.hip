@@ -83,28 +83,39 @@ __device__ __forceinline__ bf16x8 frag_tr(const unsigned char *t, int col0, int 
 }
 
 // ------------------------------------------------------------------------------------------
+constexpr int OST_PITCH = 144;                                // bytes per staged output row (128 + pad: see fwd_store)
+constexpr int OST_B = 32 * OST_PITCH;
+
 __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
                                                        bf16 *__restrict__ o_lo, float *__restrict__ lse, int S,
                                                        int H, int n_seq)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
-    // Block -> (query tile, head, sequence).  Workgroups are handed to the 8 XCDs round-robin, so the
-    // blocks of one (sequence, head) - which read the same K and V tiles - are given ids that land on ONE
-    // XCD, next to each other in dispatch order: its L2 then serves the re-reads (with the tiles of a head
-    // spread over four XCDs the kernel fetched twice its algorithmic bytes from memory).
-    const int nqt = (S + 127) >> 7;
+    __shared__ __attribute__((aligned(16))) unsigned char Ost[4 * OST_B];
+    // Block -> (two query tiles, head, sequence).  Workgroups go to the 8 XCDs round-robin and, inside an XCD,
+    // to its compute units in a fixed rotation as well: with one 128-query tile per block and tiles ordered
+    // inside a (sequence, head) pair, every compute unit kept receiving tiles of the SAME length (the rotation's
+    // period is a multiple of the tiles per pair), a 4:1 load imbalance at S = 512 that left two thirds of the
+    // block slots empty for most of the launch.  So a block takes query tiles j and nqt-1-j of its pair, the
+    // long one first: all blocks then do the same number of key tiles (nqt + 1 halves of a tile), whatever the
+    // rotation.  The blocks of one pair still get ids that land on ONE XCD, next to each other in dispatch
+    // order, so its L2 serves their re-reads of K and V.
+    const int nqt = (S + 127) >> 7, npb = (nqt + 1) >> 1;
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int pair = (idx / nqt) * 8 + xcd;             // (sequence, head) pair
+    const int pair = (idx / npb) * 8 + xcd;             // (sequence, head) pair
     if (pair >= H * n_seq) return;
-    const int qt = nqt - 1 - idx % nqt;                 // longest rows first
+    const int qtA = nqt - 1 - idx % npb, qtB = idx % npb;                 // qtA >= qtB
+    const int ntA = min(S, qtA * 128 + 128) >> 6;                       // key tiles of 64 per query tile
+    const int ntB = qtA != qtB ? (qtB * 128 + 128) >> 6 : 0;
+    const int nt = ntA + ntB;
     const int a = pair % H, n = pair / H;
     const int d = H * 64, ld = 3 * d;
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
-    const int qb = qt * 128 + wave * 32;
-    const bool active = qb < S;
-    const int q = qb + r32;
+    int qb = qtA * 128 + wave * 32;
+    bool active = qb < S;
+    int q = qb + r32;
 
     bf16x8 qf[4];
     if (active) {
@@ -125,8 +136,49 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = f2bf(1.0f);
     float m = -INFINITY;
-    const int kv_end = min(S, qt * 128 + 128);
-    const int ntile = kv_end >> 6;
+
+    // Output of one query tile: O = oacc / l, its low-order bf16 term, and the log-sum-exp.  A lane holds 4
+    // consecutive columns of ONE row per register group, so direct stores would touch 32 different 128-byte
+    // lines per instruction with 8 bytes each; the wave's 32 x 64 outputs go through a private LDS area
+    // instead (row pitch 144 bytes: rows 16 apart share banks, a 2-way conflict on the 8-byte writes) and
+    // leave as whole lines, 16 bytes per lane.  LDS operations of one wave complete in issue order, so the
+    // area needs no barrier, only that the compiler keeps the order.
+    auto fwd_store = [&]() {
+        if (!active) return;
+        unsigned char *stg = Ost + wave * OST_B;
+        const float lh = lacc[0];
+        const float inv = 1.0f / lh;
+        const int orow = lane >> 3, och = lane & 7;
+        const size_t ooff = ((size_t)n * S + qb + orow) * d + a * 64 + och * 8;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {          // 0: O, 1: its low-order term
+            bf16 *dst = pass ? o_lo : o;
+            if (!dst) break;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float v = oacc[dt][4 * e4 + i] * inv;
+                        const bf16 hi = f2bf(v);
+                        w[i] = pass ? f2bf(v - bf2f(hi)) : hi;       // o + o_lo carries ~16 bits
+                    }
+                    *(bf16x4 *)(stg + r32 * OST_PITCH + (32 * dt + 8 * e4 + 4 * g) * 2) = w;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            bf16x8 rows[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) rows[it] = *(const bf16x8 *)(stg + (8 * it + orow) * OST_PITCH + och * 16);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) *(bf16x8 *)(dst + ooff + (size_t)(8 * it) * d) = rows[it];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (g == 0) lse[((size_t)n * H + a) * S + q] = m + log2f(lh);
+    };
 
     // All 8 K fragments and all 16 V fragment reads of a tile are issued before the first MFMA, so the LDS
     // latency is paid once per tile instead of once per fragment (left inline in the MFMA calls the compiler
@@ -178,50 +230,46 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
             }                                                                                          \
         }                                                                                              \
     }
+    // Step t of the block's flat tile sequence (ntA tiles of the long query tile, then ntB of the short one);
+    // at the switch the finished tile goes out and the wave's state is set up for the other query rows.
+#define FWD_STEP(Ks, Vs, t)                                                                            \
+    {                                                                                                  \
+        if ((t) == ntA) {                                                                              \
+            fwd_store();                                                                               \
+            qb = qtB * 128 + wave * 32; q = qb + r32; active = true;                                   \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                           \
+                qf[ks] = *(const bf16x8 *)(base + (size_t)q * ld + ks * 16 + g * 8);                   \
+            oacc[0] = zero16(); oacc[1] = zero16(); lacc = zero16(); m = -INFINITY;                    \
+        }                                                                                              \
+        const int k0_ = ((t) < ntA ? (t) : (t) - ntA) * 64;                                            \
+        FWD_TILE(Ks, Vs, k0_)                                                                          \
+    }
+#define FWD_COPY(Kd, Vd, t)                                                                            \
+    {                                                                                                  \
+        const size_t off_ = (size_t)((t) < ntA ? (t) : (t) - ntA) * 64 * ld;                           \
+        tile_copy_async(Kd, kg + off_, ld, wave, lane);                                                \
+        tile_copy_async(Vd, vg + off_, ld, wave, lane);                                                \
+    }
 
     const bf16 *kg = base + d, *vg = base + 2 * d;
-    tile_copy_async(K0, kg, ld, wave, lane);
-    tile_copy_async(V0, vg, ld, wave, lane);
+    FWD_COPY(K0, V0, 0)
     AT_WAIT_VM0();
     __syncthreads();
-    int j = 0;
-    for (; j + 2 <= ntile; j += 2) {
-        tile_copy_async(K1, kg + (size_t)(j + 1) * 64 * ld, ld, wave, lane);
-        tile_copy_async(V1, vg + (size_t)(j + 1) * 64 * ld, ld, wave, lane);
-        FWD_TILE(K0, V0, j * 64)
+    for (int t = 0; t < nt; t += 2) {
+        if (t + 1 < nt) FWD_COPY(K1, V1, t + 1)
+        FWD_STEP(K0, V0, t)
         AT_WAIT_VM0();
         __syncthreads();
-        if (j + 2 < ntile) {
-            tile_copy_async(K0, kg + (size_t)(j + 2) * 64 * ld, ld, wave, lane);
-            tile_copy_async(V0, vg + (size_t)(j + 2) * 64 * ld, ld, wave, lane);
-        }
-        FWD_TILE(K1, V1, (j + 1) * 64)
+        if (t + 1 >= nt) break;
+        if (t + 2 < nt) FWD_COPY(K0, V0, t + 2)
+        FWD_STEP(K1, V1, t + 1)
         AT_WAIT_VM0();
         __syncthreads();
     }
-    if (j < ntile) FWD_TILE(K0, V0, j * 64)
+#undef FWD_COPY
+#undef FWD_STEP
 #undef FWD_TILE
-
-    if (active) {
-        const float lh = lacc[0];
-        const float inv = 1.0f / lh;
-        const size_t ooff = ((size_t)n * S + q) * d + a * 64;
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                bf16x4 w, wl;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float v = oacc[dt][4 * e4 + i] * inv;
-                    w[i] = f2bf(v);
-                    wl[i] = f2bf(v - bf2f(w[i]));       // second bf16 term: o + o_lo carries ~16 bits
-                }
-                *(bf16x4 *)(o + ooff + 32 * dt + 8 * e4 + 4 * g) = w;
-                if (o_lo) *(bf16x4 *)(o_lo + ooff + 32 * dt + 8 * e4 + 4 * g) = wl;
-            }
-        if (g == 0) lse[((size_t)n * H + a) * S + q] = m + log2f(lh);
-    }
+    fwd_store();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -695,7 +743,7 @@ int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq,
 {
     if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return SL_EINVAL;
     const long long pairs8 = ((long long)H * n_seq + 7) / 8 * 8;
-    const long long nblk = pairs8 * ((S + 127) / 128);
+    const long long nblk = pairs8 * (((S + 127) / 128 + 1) / 2);     // two query tiles of 128 per block
     if (nblk > 0x7fffffffLL) return SL_EINVAL;
     // algorithmic work: two products over the lower triangle, 2 S d flop per token (d = 64 H)
     const bool rec = prof_begin(PK_ATTN_FWD, st);
