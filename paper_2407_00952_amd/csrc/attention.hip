@@ -538,8 +538,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
 //   * dS of a query tile is written to LDS as dS^T [key][32 queries] bf16; after one barrier the 8
 //     waves each form one 16 x 16 piece of dQ = dS K over all visible keys (phase 2), in a fixed
 //     order -- no floating-point atomics, results stay bit-reproducible.
-//   * Q / dO tiles (4 KB each) are double buffered asynchronous copies, dS^T is double buffered too,
-//     so there is one barrier per query tile: phase 2 of tile i runs next to phase 1 of tile i + 1.
+//   * Q / dO tiles (4 KB each) are double buffered asynchronous copies that also bring the tile's 32 K rows,
+//     dS^T is double buffered too, so there is one barrier per query tile: phase 2 of tile i runs next to
+//     phase 1 of tile i + 1.
+//   * Before the arithmetic starts the block waits for one round of memory traffic: the first tile, the
+//     wave's V fragments, and the operands of delta = rowsum(dO * O) of all rows, every load of which is
+//     issued before the first is used.  (All blocks of a launch run in step, so this round is read by every
+//     compute unit at once, at the memory's speed, with the matrix cores idle; forming delta tile by tile
+//     behind the arithmetic, from rows streamed into LDS, was measured and only moved the same time into the
+//     steps, whose length is set by the latency of the tile copies.)
 constexpr int FB_MAXS = 512;
 
 // XOR mask of the 8-byte slots of a dS^T row (64 bytes = 32 queries): conflict-free both for the
@@ -566,48 +573,55 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
     const bf16 *dbase = dout + (size_t)n * S * d + a * 64;
     const int nb = S >> 5;                               // 32-row blocks (even: S is a multiple of 64)
 
-    // ---- prologue: K -> LDS, per-row statistics, this wave's V fragments, first query tile
-    {
-        const int lrow = lane >> 3, lch = (lane & 7) ^ swm(lane >> 3);
-        for (int pc = wave; pc < (S >> 3); pc += 8)      // 1 KB pieces of 8 rows
-            AT_GLDS(base + d + (size_t)(pc * 8 + lrow) * ld + lch * 8, Ks + pc * 1024);
+    // one 1 KB piece per wave and tile of Q (waves 0-3) and dO (waves 4-7), and the tile's 32 K rows (waves 0-3)
+#define FB_COPY(Qd, Dd, it)                                                                            \
+    {                                                                                                  \
+        const int lrow_c = lane >> 3, lch_c = (lane & 7) ^ swm(lane >> 3);                             \
+        const int row_c = 32 * (it) + (wave & 3) * 8 + lrow_c;                                         \
+        if (wave < 4) {                                                                                \
+            AT_GLDS(base + (size_t)row_c * ld + lch_c * 8, (Qd) + (wave & 3) * 1024);                  \
+            AT_GLDS(base + d + (size_t)row_c * ld + lch_c * 8, Ks + (it) * 4096 + (wave & 3) * 1024);  \
+        } else AT_GLDS(dbase + (size_t)row_c * d + lch_c * 8, (Dd) + (wave & 3) * 1024);               \
     }
+    // ---- prologue: first tile (Q, dO, K rows), log-sum-exp and delta of all rows, this wave's V fragments
+    FB_COPY(Qb0, Db0, 0)
     if (tid < S) lse_s[tid] = lse[((size_t)n * H + a) * S + tid];
-    // delta = rowsum(dO * (O + O_lo)): 8 lanes per row (16 bytes each, one full 128-byte line per row and
-    // operand), 64 rows per pass, reduced with three shuffles
-    for (int r0 = 0; r0 < S; r0 += 64) {
-        const size_t off_d = ((size_t)n * S + r0 + (tid >> 3)) * d + a * 64 + (tid & 7) * 8;
-        const bf16x8 dv = *(const bf16x8 *)(dout + off_d);
-        const bf16x8 ov = *(const bf16x8 *)(o + off_d);
-        const bf16x8 lv = *(const bf16x8 *)(o_lo + off_d);
-        float dl = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dl += bf2f(dv[i]) * (bf2f(ov[i]) + bf2f(lv[i]));
-        dl += __shfl_xor(dl, 1, 64);
-        dl += __shfl_xor(dl, 2, 64);
-        dl += __shfl_xor(dl, 4, 64);
-        if ((tid & 7) == 0) dl_s[r0 + (tid >> 3)] = dl;
-    }
     const bool owner = wave < (nb >> 1);                 // waves beyond the number of block pairs only do phase 2
     const int jb[2] = {wave, nb - 1 - wave};
     bf16x8 vf[2][4];
-    f32x16 dkacc[2][2], dvacc[2][2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int key = min(32 * jb[b] + r32, S - 1);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
             vf[b][ks] = *(const bf16x8 *)(base + 2 * d + (size_t)(owner ? key : 0) * ld + ks * 16 + g * 8);
-        dkacc[b][0] = zero16(); dkacc[b][1] = zero16(); dvacc[b][0] = zero16(); dvacc[b][1] = zero16();
     }
-    // one 1 KB piece per wave and tile: waves 0-3 copy the Q rows, waves 4-7 the dO rows
-#define FB_COPY(Qd, Dd, it)                                                                            \
-    {                                                                                                  \
-        const int lrow_c = lane >> 3, lch_c = (lane & 7) ^ swm(lane >> 3);                             \
-        const int row_c = 32 * (it) + (wave & 3) * 8 + lrow_c;                                         \
-        if (wave < 4) AT_GLDS(base + (size_t)row_c * ld + lch_c * 8, (Qd) + (wave & 3) * 1024);        \
-        else AT_GLDS(dbase + (size_t)row_c * d + lch_c * 8, (Dd) + (wave & 3) * 1024);                 \
+    {
+        // delta = rowsum(dO * (O + O_lo)): 8 lanes per row (16 bytes each, one full 128-byte line per row and
+        // operand), 64 rows per pass, reduced with three shuffles; the loads of all passes go out first
+        bf16x8 dv[FB_MAXS / 64], ov[FB_MAXS / 64], lv[FB_MAXS / 64];
+        const size_t off_d = ((size_t)n * S + (tid >> 3)) * d + a * 64 + (tid & 7) * 8;
+#pragma unroll
+        for (int ps = 0; ps < FB_MAXS / 64; ++ps)
+            if (64 * ps < S) {
+                dv[ps] = *(const bf16x8 *)(dout + off_d + (size_t)64 * ps * d);
+                ov[ps] = *(const bf16x8 *)(o + off_d + (size_t)64 * ps * d);
+                lv[ps] = *(const bf16x8 *)(o_lo + off_d + (size_t)64 * ps * d);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ps = 0; ps < FB_MAXS / 64; ++ps)
+            if (64 * ps < S) {
+                float dl = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dl += bf2f(dv[ps][i]) * (bf2f(ov[ps][i]) + bf2f(lv[ps][i]));
+                dl += __shfl_xor(dl, 1, 64);
+                dl += __shfl_xor(dl, 2, 64);
+                dl += __shfl_xor(dl, 4, 64);
+                if ((tid & 7) == 0) dl_s[64 * ps + (tid >> 3)] = dl;
+            }
     }
+    f32x16 dkacc[2][2], dvacc[2][2];
     // phase 1 for query tile `it` (rows 32 it ..) against this wave's blocks that it can see.  Only the
     // block on the diagonal (j == it) needs the causal mask; the blocks below it run a copy without it.
 #define FB_BLOCK(Qs, Ds, dSw, it, b, j, DIAG)                                                          \
@@ -690,14 +704,15 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
         *(bf16x4 *)(dqkv + ((size_t)n * S + q) * ld + a * 64 + 16 * p2_dt + 4 * kg) = w4;              \
     }
 
-    FB_COPY(Qb0, Db0, 0)
     AT_WAIT_VM0();
-    __syncthreads();                                     // K, statistics of tile 0 and tile 0 are in LDS
+    __syncthreads();                                     // tile 0, its K rows and the statistics it needs are in LDS
     if (nb > 1) FB_COPY(Qb1, Db1, 1)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) { dkacc[b][0] = zero16(); dkacc[b][1] = zero16(); dvacc[b][0] = zero16(); dvacc[b][1] = zero16(); }
     FB_PHASE1(Qb0, Db0, dS0, 0)
     for (int it = 0; it < nb; it += 2) {
         AT_WAIT_VM0();
-        __syncthreads();                                 // dS^T of tile it complete; tile it + 1 and its delta landed
+        __syncthreads();                                 // dS^T of tile it complete; tile it + 1 and its K rows landed
         if (it + 2 < nb) FB_COPY(Qb0, Db0, it + 2)
         FB_PHASE2(dS0, it)
         if (it + 1 < nb) FB_PHASE1(Qb1, Db1, dS1, it + 1)
@@ -714,25 +729,39 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
 #undef FB_BLOCK
 #undef FB_PHASE2
 
+    // dK, dV of the two key blocks leave through LDS (the dS^T buffers, free after one more barrier) as whole
+    // 128-byte lines: a lane holds 4 consecutive columns of one key per register group, direct stores would
+    // touch 32 lines per instruction with 8 bytes each
+    __syncthreads();
     if (owner) {
+        unsigned char *stg = wave < 4 ? dS0 + wave * OST_B : dS1 + (wave - 4) * OST_B;      // 4.5 KB per wave
+        const int orow = lane >> 3, och = lane & 7;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            const int key = 32 * jb[b] + r32;
-            bf16 *krow = dqkv + ((size_t)n * S + key) * ld + d + a * 64;
-            bf16 *vrow = krow + d;
+            bf16 *out = dqkv + ((size_t)n * S + 32 * jb[b] + orow) * ld + d + a * 64 + och * 8;
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
+            for (int which = 0; which < 2; ++which) {     // 0: dK (scaled), 1: dV
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    bf16x4 wk, wv;
+                for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        wk[i] = f2bf(dkacc[b][dt][4 * e4 + i] * 0.125f);
-                        wv[i] = f2bf(dvacc[b][dt][4 * e4 + i]);
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        bf16x4 w;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            w[i] = which ? f2bf(dvacc[b][dt][4 * e4 + i]) : f2bf(dkacc[b][dt][4 * e4 + i] * 0.125f);
+                        *(bf16x4 *)(stg + r32 * OST_PITCH + (32 * dt + 8 * e4 + 4 * g) * 2) = w;
                     }
-                    *(bf16x4 *)(krow + 32 * dt + 8 * e4 + 4 * g) = wk;
-                    *(bf16x4 *)(vrow + 32 * dt + 8 * e4 + 4 * g) = wv;
-                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                bf16x8 rows[4];
+#pragma unroll
+                for (int it = 0; it < 4; ++it)
+                    rows[it] = *(const bf16x8 *)(stg + (8 * it + orow) * OST_PITCH + och * 16);
+#pragma unroll
+                for (int it = 0; it < 4; ++it) *(bf16x8 *)(out + (size_t)(8 * it) * ld + which * d) = rows[it];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
         }
     }
 }

@@ -16,7 +16,12 @@ test suite instead of corrupting results:
      longest, 16-pass, matrix instruction; the 16x16x32 bf16 one needs fewer) pass before the first
      instruction other than an MFMA that reads or writes an accumulation register;
   4. M0 is written only by the copy sequence (s_mov_b32 m0 / s_nop 0 / global_load_lds_*) and read by
-     nothing else, in gemm.hip and mx.hip.
+     nothing else, in gemm.hip and mx.hip;
+  5. no vector memory instruction reads a scalar register that a vector instruction (v_readlane,
+     v_readfirstlane, a compare with a scalar destination) wrote fewer than 5 wait states earlier.  The
+     compiler keeps that distance for its own instructions but does not look into inline assembly, and the
+     copies take their base address in scalar registers: a spilled scalar restored right in front of one
+     would make it read a stale address.
 """
 import os
 import re
@@ -175,3 +180,56 @@ def _check_m0(text, what):
 def test_m0_is_only_used_by_the_async_copies(gemm_asm):
     _check_m0(gemm_asm, "gemm.hip")
     _check_m0(_assembly("mx.hip"), "mx.hip")
+
+
+_SREG = re.compile(r"\bs(\d+)\b|\bs\[(\d+):(\d+)\]")
+_VMEM = ("global_load", "global_store", "global_atomic", "buffer_load", "buffer_store", "scratch_load", "scratch_store")
+
+
+def _sregs(text):
+    regs = set()
+    for m in _SREG.finditer(text):
+        if m.group(1) is not None:
+            regs.add(int(m.group(1)))
+        else:
+            regs.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return regs
+
+
+def _valu_scalar_dest(ins):
+    """Scalar registers written by a vector instruction (empty for everything else)."""
+    op = ins.split()[0]
+    if op.startswith(("v_readlane_b32", "v_readfirstlane_b32")) or (op.startswith("v_cmp") and op.endswith("_e64")):
+        return _sregs(ins.split(None, 1)[1].split(",")[0])
+    return set()
+
+
+def _check_valu_sgpr_to_vmem(text, what):
+    for name, body in _functions(text).items():
+        code = [ins for ins in body if not _is_label(ins)]
+        for i, ins in enumerate(code):
+            if not ins.startswith(_VMEM):
+                continue
+            used = _sregs(ins)
+            if not used:
+                continue
+            ws, j = 0, i - 1
+            while j >= 0 and ws < 5:
+                hit = _valu_scalar_dest(code[j]) & used
+                assert not hit, (what, name, code[j], ins, "only %d wait states between" % ws)
+                ws += _wait_states(code[j])
+                j -= 1
+
+
+def test_vector_written_scalars_are_settled_before_vector_memory_reads_them(gemm_asm):
+    _check_valu_sgpr_to_vmem(gemm_asm, "gemm.hip")
+    _check_valu_sgpr_to_vmem(_assembly("mx.hip"), "mx.hip")
+    _check_valu_sgpr_to_vmem(_assembly("attention.hip"), "attention.hip")
+
+
+def test_the_scalar_hazard_check_sees_a_planted_hazard():
+    bad = ("_Z3foov:\n\tv_readlane_b32 s0, v255, 16\n\tv_readlane_b32 s1, v255, 17\n\tv_readlane_b32 s51, v255, 19\n"
+           "\tglobal_load_dwordx4 v[178:181], v221, s[0:1]\n\ts_endpgm\n.Lfunc_end0:\n")
+    with pytest.raises(AssertionError):
+        _check_valu_sgpr_to_vmem(bad, "planted")
+    _check_valu_sgpr_to_vmem(bad.replace("\tglobal_load", "\ts_nop 4\n\tglobal_load"), "planted, with wait states")
