@@ -235,10 +235,14 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
 #define FWD_STEP(Ks, Vs, t)                                                                            \
     {                                                                                                  \
         if ((t) == ntA) {                                                                              \
+            /* the short tile's Q rows have been waiting in this wave's output staging area since the   \
+               first copies: fetched from memory here they would cost the block one exposed latency */  \
+            bf16x8 qn[4];                                                                              \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) qn[ks] = frag_rm(Ost + wave * OST_B, r32, ks, g); \
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   /* read before fwd_store overwrites */ \
             fwd_store();                                                                               \
             qb = qtB * 128 + wave * 32; q = qb + r32; active = true;                                   \
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                           \
-                qf[ks] = *(const bf16x8 *)(base + (size_t)q * ld + ks * 16 + g * 8);                   \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) qf[ks] = qn[ks];                          \
             oacc[0] = zero16(); oacc[1] = zero16(); lacc = zero16(); m = -INFINITY;                    \
         }                                                                                              \
         const int k0_ = ((t) < ntA ? (t) : (t) - ntA) * 64;                                            \
@@ -253,6 +257,12 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
 
     const bf16 *kg = base + d, *vg = base + 2 * d;
     FWD_COPY(K0, V0, 0)
+    if (ntB > 0) {                                       // this wave's 32 Q rows of the short tile -> its staging area
+        const int lrow = lane >> 3, lch = (lane & 7) ^ swm(lane >> 3);
+        const bf16 *qsrc = base + (size_t)(qtB * 128 + wave * 32) * ld;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) AT_GLDS(qsrc + (size_t)(p * 8 + lrow) * ld + lch * 8, Ost + wave * OST_B + p * 1024);
+    }
     AT_WAIT_VM0();
     __syncthreads();
     for (int t = 0; t < nt; t += 2) {
