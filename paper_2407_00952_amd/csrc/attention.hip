@@ -125,16 +125,15 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
     f32x16 oacc[2] = {zero16(), zero16()};
     // The softmax is VALU-bound at head size 64, so the per-element work is kept to one FMA, one
     // exp2 and a share of a max and of a bf16 pack:
-    //  * the row sum is taken by the matrix core: an all-ones A operand against the bf16
-    //    probabilities gives sum_k P[k][q] in every row of `lacc`; only element 0 is kept consistent
-    //    (rescaled), the other rows are never read.  Summing the ROUNDED probabilities also makes O an
-    //    exact convex combination of V rows, which the backward's rowsum(dO*O) relies on.
+    //  * the row sum is taken over the bf16-ROUNDED probabilities, two per instruction (bf16 dot product
+    //    against (1, 1) with an fp32 addend); a lane sums the keys it holds, the two lanes of a query are
+    //    added at the end.  Summing the rounded values makes O an exact convex combination of V rows, which
+    //    the backward's rowsum(dO*O) relies on.  (An all-ones MFMA did the same for 16 registers and 128
+    //    cycles of the matrix pipe per tile.)
     //  * the running maximum m (log2 units, scaled) is only raised when a tile exceeds it by more
     //    than 8, so most tiles skip the rescaling of the accumulators; p <= 2^8 meanwhile.
-    f32x16 lacc = zero16();
-    bf16x8 ones;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ones[i] = f2bf(1.0f);
+    float lsum = 0.f;
+    const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
     float m = -INFINITY;
 
     // Output of one query tile: O = oacc / l, its low-order bf16 term, and the log-sum-exp.  A lane holds 4
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
     auto fwd_store = [&]() {
         if (!active) return;
         unsigned char *stg = Ost + wave * OST_B;
-        const float lh = lacc[0];
+        const float lh = lsum + __shfl_xor(lsum, 32, 64);
         const float inv = 1.0f / lh;
         const int orow = lane >> 3, och = lane & 7;
         const size_t ooff = ((size_t)n * S + qb + orow) * d + a * 64 + och * 8;
@@ -208,7 +207,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
             const float m_new = fmaxf(m, tmax);                                                        \
             const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                     \
             m = m_new;                                                                                 \
-            lacc[0] *= alpha;                                                                          \
+            lsum *= alpha;                                                                             \
             _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                           \
                 _Pragma("unroll") for (int e = 0; e < 16; ++e) oacc[dt][e] *= alpha;                   \
         }                                                                                              \
@@ -224,7 +223,10 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
                 _Pragma("unroll") for (int i = 0; i < 8; ++i) pe[i] = fmaf(sacc[mt][8 * hh + i], kScaleLog2, -m); \
                 _Pragma("unroll") for (int i = 0; i < 8; ++i) pe[i] = __builtin_amdgcn_exp2f(pe[i]);   \
                 _Pragma("unroll") for (int i = 0; i < 8; ++i) pb[i] = f2bf(pe[i]);                     \
-                lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, lacc, 0, 0, 0);               \
+                _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
+                    const bf16x2 pr = {pb[2 * i], pb[2 * i + 1]};                                    \
+                    lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, lsum, false);                    \
+                }                                                                                      \
                 _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                       \
                     oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hh][dt], pb, oacc[dt], 0, 0, 0); \
             }                                                                                          \
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
             fwd_store();                                                                               \
             qb = qtB * 128 + wave * 32; q = qb + r32; active = true;                                   \
             _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) qf[ks] = qn[ks];                          \
-            oacc[0] = zero16(); oacc[1] = zero16(); lacc = zero16(); m = -INFINITY;                    \
+            oacc[0] = zero16(); oacc[1] = zero16(); lsum = 0.f; m = -INFINITY;                    \
         }                                                                                              \
         const int k0_ = ((t) < ntA ? (t) : (t) - ntA) * 64;                                            \
         FWD_TILE(Ks, Vs, k0_)                                                                          \
