@@ -286,24 +286,31 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_kernel(const bf16 *__restrict
 
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O), which the dK/dV kernel reads afterwards)
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ o,
+__global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ o,
                                                           const bf16 *__restrict__ o_lo,
                                                           const bf16 *__restrict__ dout,
                                                           const float *__restrict__ lse, float *__restrict__ delta,
                                                           bf16 *__restrict__ dqkv, int S, int H, int n_seq)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char K0[TILE_B], V0[TILE_B], K1[TILE_B], V1[TILE_B];
-    // block ids decoded as in the forward: the query tiles of a (sequence, head) share an XCD
-    const int nqt = (S + 127) >> 7;
+    // block ids decoded as in the forward: the query tiles of a (sequence, head) share an XCD, and a block
+    // takes the tiles j and nqt-1-j one after the other so that every block has the same work
+    const int nqt = (S + 127) >> 7, npb = (nqt + 1) >> 1;
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int pair = (idx / nqt) * 8 + xcd;
+    const int pair = (idx / npb) * 8 + xcd;
     if (pair >= H * n_seq) return;
-    const int qt = nqt - 1 - idx % nqt;
     const int a = pair % H, n = pair / H;
     const int d = H * 64, ld = 3 * d;
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
+#pragma clang loop unroll(disable)
+    for (int ph = 0; ph < 2; ++ph) {
+    const int qt = ph == 0 ? nqt - 1 - idx % npb : idx % npb;
+    if (ph == 1) {
+        if (qt == nqt - 1 - idx % npb) break;            // odd tile count: the middle tile stands alone
+        __syncthreads();                                 // the first pass's tiles are no longer read
+    }
     const int qb = qt * 128 + wave * 32;
     const bool active = qb < S;
     const int q = qb + r32;
@@ -395,6 +402,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
                 *(bf16x4 *)(drow + 32 * dt + 8 * e4 + 4 * g) = w;
             }
     }
+    }   // pass
 }
 
 // ------------------------------------------------------------------------------------------
@@ -407,12 +415,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
 {
     __shared__ __attribute__((aligned(1024))) unsigned char Q0[TILE_B], D0[TILE_B], Q1[TILE_B], D1[TILE_B];
     __shared__ __align__(16) float st0[128], st1[128];   // lse | delta of the 64 queries of a tile
-    // block ids decoded as in the forward: the key tiles of a (sequence, head) share an XCD
-    const int nkt = (S + 127) >> 7;
+    // block ids decoded as in the forward: the key tiles of a (sequence, head) share an XCD, and a block takes
+    // the tiles j (most query tiles to walk) and nkt-1-j one after the other: equal work per block
+    const int nkt = (S + 127) >> 7, npb = (nkt + 1) >> 1;
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int pair = (idx / nkt) * 8 + xcd;
+    const int pair = (idx / npb) * 8 + xcd;
     if (pair >= H * n_seq) return;
-    const int kvt = idx % nkt;                           // keys kvt*128 ..: most work first
     const int a = pair % H, n = pair / H;
     const int d = H * 64, ld = 3 * d;
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
@@ -420,6 +428,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
     const bf16 *base = qkv + (size_t)n * S * ld + a * 64;
     const bf16 *dbase = dout + (size_t)n * S * d + a * 64;
     const float *lse_b = lse + ((size_t)n * H + a) * S, *dl_b = delta + ((size_t)n * H + a) * S;
+#pragma clang loop unroll(disable)
+    for (int ph = 0; ph < 2; ++ph) {
+    const int kvt = ph == 0 ? idx % npb : nkt - 1 - idx % npb;
+    if (ph == 1) {
+        if (kvt == idx % npb) break;                     // odd tile count: the middle tile stands alone
+        __syncthreads();                                 // the first pass's tiles and statistics are no longer read
+    }
     const int kb = kvt * 128 + wave * 32;
     const bool active = kb < S;
     const int key = kb + r32;
@@ -538,6 +553,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
                 *(bf16x4 *)(vrow + 32 * dt + 8 * e4 + 4 * g) = wv;
             }
     }
+    }   // pass
 }
 
 // ------------------------------------------------------------------------------------------
@@ -808,7 +824,7 @@ int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16
         return 0;
     }
     const long long pairs8 = ((long long)H * n_seq + 7) / 8 * 8;
-    const long long nblk = pairs8 * ((S + 127) / 128);
+    const long long nblk = pairs8 * (((S + 127) / 128 + 1) / 2);     // two tiles of 128 rows per block
     if (nblk > 0x7fffffffLL) return SL_EINVAL;
     const dim3 grid((unsigned)nblk);
     hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, dim3(256), 0, st, qkv, o, o_lo, dout, lse, delta, dqkv, S, H, n_seq);
