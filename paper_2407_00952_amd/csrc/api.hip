@@ -716,6 +716,7 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
             return rc;
         // do = dh' Wo (+ adapter)
         bf16 *dob = at<bf16>(c, c->t_do);
+        bool gemm_delta = false;
         {
             GemmArgs a = gemm_base(dh1_16, d, at<bf16>(c, b.WoT), T, d, d, nullptr, c->s);
             a.out0 = dob;
@@ -726,13 +727,19 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
             }
             MxOperands mxo;
             set_mx(c, l, MXW_OT, a, mxo, 1);
-            if ((rc = launch_gemm(a, EPI_STORE, ad ? 16 : 0, st))) return rc;
+            // where the 4-wave kernel runs this product and the fused attention backward follows, the epilogue also
+            // forms delta = rowsum(dO * O) per head, [T, H]
+            gemm_delta = !ad && !c->mx && attn_bwd_takes_delta(c->S);
+            if (gemm_delta) {
+                a.dl_o = at<bf16>(c, b.o); a.dl_lo = at<bf16>(c, b.o_lo); a.dl_out = at<float>(c, c->t_delta);
+            }
+            if ((rc = launch_gemm(a, gemm_delta ? EPI_STORE_DELTA : EPI_STORE, ad ? 16 : 0, st))) return rc;
             if (ad && (rc = lora_grads(c, l, SLORA_PROJ_O, at<bf16>(c, b.o), d, dh1_16, d, ps, SL_RP, st))) return rc;
         }
         // attention backward
         bf16 *dqkv = at<bf16>(c, c->t_dqkv);
         if ((rc = launch_attn_bwd(at<bf16>(c, b.qkv), at<bf16>(c, b.o), at<bf16>(c, b.o_lo), dob, at<float>(c, b.lse),
-                                  at<float>(c, c->t_delta), dqkv, c->n_seq, c->S, c->H, st)))
+                                  at<float>(c, c->t_delta), dqkv, c->n_seq, c->S, c->H, st, gemm_delta)))
             return rc;
         // du = [dq dk dv] Wqkv (+ adapters): one GEMM with contraction 3d
         bf16 *dub = at<bf16>(c, c->t_du);

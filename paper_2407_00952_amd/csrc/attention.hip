@@ -586,7 +586,7 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
                                                              const bf16 *__restrict__ o_lo,
                                                              const bf16 *__restrict__ dout,
                                                              const float *__restrict__ lse, bf16 *__restrict__ dqkv,
-                                                             int S, int H)
+                                                             int S, int H, const float *__restrict__ delta_in)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char Ks[FB_MAXS * 128];
     __shared__ __attribute__((aligned(1024))) unsigned char dS0[FB_MAXS * 64], dS1[FB_MAXS * 64];
@@ -624,8 +624,12 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16 *__restr
         for (int ks = 0; ks < 4; ++ks)
             vf[b][ks] = *(const bf16x8 *)(base + 2 * d + (size_t)(owner ? key : 0) * ld + ks * 16 + g * 8);
     }
-    {
-        // delta = rowsum(dO * (O + O_lo)): 8 lanes per row (16 bytes each, one full 128-byte line per row and
+    // delta = rowsum(dO * (O + O_lo)): [T, H] from the product that formed dO (its epilogue has dO in registers
+    // and reads O there, which saves this kernel a second pass over dO and half of its prologue's traffic), or
+    if (delta_in != nullptr) {
+        if (tid < S) dl_s[tid] = delta_in[((size_t)n * S + tid) * H + a];
+    } else {
+        // formed here: 8 lanes per row (16 bytes each, one full 128-byte line per row and
         // operand), 64 rows per pass, reduced with three shuffles; the loads of all passes go out first
         bf16x8 dv[FB_MAXS / 64], ov[FB_MAXS / 64], lv[FB_MAXS / 64];
         const size_t off_d = ((size_t)n * S + (tid >> 3)) * d + a * 64 + (tid & 7) * 8;
@@ -810,15 +814,19 @@ int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq,
     return 0;
 }
 
+bool attn_bwd_takes_delta(int S) { return S > 0 && S <= FB_MAXS && (S % 64) == 0; }
+
 int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16 *dout, const float *lse,
-                    float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st)
+                    float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st, bool delta_ready)
 {
+    if (delta_ready && !attn_bwd_takes_delta(S)) return SL_EINVAL;
     if (n_seq <= 0 || S <= 0 || (S % 64) || H <= 0) return SL_EINVAL;
     // algorithmic work: four products over the lower triangle (the recomputed scores are not counted)
     const double work = 4.0 * S * 64.0 * H * ((double)n_seq * S);
     const bool rec = prof_begin(PK_ATTN_BWD, st);
     if (S <= FB_MAXS) {
-        hipLaunchKernelGGL(attn_bwd_fused_kernel, dim3(H, n_seq), dim3(512), 0, st, qkv, o, o_lo, dout, lse, dqkv, S, H);
+        hipLaunchKernelGGL(attn_bwd_fused_kernel, dim3(H, n_seq), dim3(512), 0, st, qkv, o, o_lo, dout, lse, dqkv, S, H,
+                           delta_ready ? (const float *)delta : nullptr);
         prof_end(rec, PK_ATTN_BWD, work, st);
         SL_CHECK_LAUNCH("attn_bwd_fused");
         return 0;

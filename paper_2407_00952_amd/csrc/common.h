@@ -66,7 +66,9 @@ struct EmbedSrc {
 };
 
 // ---- GEMM ---------------------------------------------------------------------------------
-enum { EPI_STORE = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_DGELU = 3 };
+// EPI_STORE_DELTA: plain store of a [M, 64 H] tensor that is the gradient of an attention output, plus
+// delta[row][head] = sum over the head's 64 columns of out * (dl_o + dl_lo) (4-wave kernel only)
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_DGELU = 3, EPI_STORE_DELTA = 4 };
 
 // Compressed mode of a context: the frozen operand of a GEMM as MXFP8 codes + block scales (packed once),
 // and scratch for the codes + scales of its activation operand, which is converted right before the launch.
@@ -89,6 +91,7 @@ struct GemmArgs {
     int K2; float zscale;            // K2 = NZ
     // epilogue
     void *out0; void *out1; const void *aux; int ldo;
+    const bf16 *dl_o, *dl_lo; float *dl_out;   // EPI_STORE_DELTA: the two bf16 terms of O [M,ldo], delta [M,N/64] fp32
     const MxOperands *mx;            // null: bf16 product.  Else: the product runs on the fp8 matrix cores
     // compressed mode only: also write the bf16 tensor of the epilogue (GELU: out1, DGELU: out0) as MXFP8
     // codes [M,ldo] + scales [M,ldo/32], so that the product that consumes it needs no conversion pass
@@ -114,8 +117,11 @@ int launch_ln_bwd(const bf16 *du, const float *h, const float *stats, const bf16
                   const ClientTable *scatter, int T, int d, hipStream_t st, unsigned char *o_codes = nullptr,
                   unsigned char *o_scales = nullptr);   // optional MXFP8 copy of out_bf16
 int launch_attn_fwd(const bf16 *qkv, bf16 *o, bf16 *o_lo, float *lse, int n_seq, int S, int H, hipStream_t st);
+// whether the backward at this sequence length takes delta = rowsum(dO * O) as an input ([T, H] fp32, filled by the
+// product that forms dO) instead of forming it itself
+bool attn_bwd_takes_delta(int S);
 int launch_attn_bwd(const bf16 *qkv, const bf16 *o, const bf16 *o_lo, const bf16 *dout, const float *lse,
-                    float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st);
+                    float *delta, bf16 *dqkv, int n_seq, int S, int H, hipStream_t st, bool delta_ready = false);
 // G[c, j] = sum_t X[t, c] * Y[t, j], j < r; written transposed ([r, C]) when out_is_rxC.
 int launch_lora_grad(const bf16 *X, int ldx, int C, const bf16 *Y, int ldy, int r, int T,
                      float *partials, float *out, int out_is_rxC, hipStream_t st);

@@ -635,6 +635,9 @@ static int launch_gemm_inner(const GemmArgs &a, int epi, int nz, hipStream_t st)
     case EPI_RESID: return launch_e<EPI_RESID>(a, nz, st);
     case EPI_GELU: return launch_e<EPI_GELU>(a, nz, st);
     case EPI_DGELU: return launch_e<EPI_DGELU>(a, nz, st);
+    case EPI_STORE_DELTA:                                // 4-wave kernel only, whole heads of 64 columns
+        if (nz != 0 || !a.dl_o || !a.dl_lo || !a.dl_out || !a.out0 || (a.N % 64) || a.nseg != 1) return SL_EINVAL;
+        return launch_t4<EPI_STORE_DELTA>(a, st);
     }
     return SL_EINVAL;
 }

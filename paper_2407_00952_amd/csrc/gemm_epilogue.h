@@ -9,7 +9,8 @@
 // fetched one 32-row strip ahead of their use so that their latency hides behind the LDS transpose.
 struct AuxRow {
     float4 r0, r1;       // EPI_RESID: 8 fp32 residual values
-    bf16x8 f;            // EPI_DGELU: 8 bf16 values of GELU'(f) saved by the forward
+    bf16x8 f;            // EPI_DGELU: 8 bf16 values of GELU'(f) saved by the forward; EPI_STORE_DELTA: 8 values of O
+    bf16x8 f2;           // EPI_STORE_DELTA: the low-order bf16 term of the same 8 values of O
 };
 
 template <int EPI, class Args>
@@ -27,6 +28,14 @@ __device__ __forceinline__ void load_aux(const Args &a, int row, int col, bool o
 #pragma unroll
         for (int i = 0; i < 8; ++i) x.f[i] = f2bf(0.f);
         if (ok) x.f = *(const bf16x8 *)((const bf16 *)a.aux + (size_t)row * a.ldo + col);
+    }
+    if constexpr (EPI == EPI_STORE_DELTA) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { x.f[i] = f2bf(0.f); x.f2[i] = f2bf(0.f); }
+        if (ok) {
+            x.f = *(const bf16x8 *)(a.dl_o + (size_t)row * a.ldo + col);
+            x.f2 = *(const bf16x8 *)(a.dl_lo + (size_t)row * a.ldo + col);
+        }
     }
 }
 
@@ -59,7 +68,24 @@ template <int EPI, class Args>
 __device__ __forceinline__ void store_row8(const Args &a, int row, int col, float (&v)[8], const AuxRow &x)
 {
     const size_t o = (size_t)row * a.ldo + col;
-    if (EPI == EPI_STORE) {
+    if constexpr (EPI == EPI_STORE_DELTA) {
+        // the rounded values that are stored also enter delta, so that the attention backward's dP (formed from
+        // the stored tensor) and delta cancel exactly where they should.  The 8 lanes that hold a head's 64
+        // columns of this row are neighbours, all active or all not (column limits are multiples of 64): after
+        // lane shifts by 1, 2 and 4 inside a row of 16 lanes, lane 7 of each group of 8 holds the group's sum.
+        bf16x8 w;
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w[i] = f2bf(v[i]);
+            p += bf2f(w[i]) * (bf2f(x.f[i]) + bf2f(x.f2[i]));
+        }
+        *(bf16x8 *)((bf16 *)a.out0 + o) = w;
+        p += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(p), 0x111, 0xF, 0xF, true));   // row_shr:1
+        p += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(p), 0x112, 0xF, 0xF, true));   // row_shr:2
+        p += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(p), 0x114, 0xF, 0xF, true));   // row_shr:4
+        if ((threadIdx.x & 7) == 7) a.dl_out[(size_t)row * (a.N >> 6) + (col >> 6)] = p;
+    } else if (EPI == EPI_STORE) {
         bf16x8 w;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w[i] = f2bf(v[i]);
