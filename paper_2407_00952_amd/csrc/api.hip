@@ -727,9 +727,9 @@ static int stack_bwd(slora_ctx *c, const void *dy, const ClientTable *tabp, hipS
             }
             MxOperands mxo;
             set_mx(c, l, MXW_OT, a, mxo, 1);
-            // where the 4-wave kernel runs this product and the fused attention backward follows, the epilogue also
-            // forms delta = rowsum(dO * O) per head, [T, H]
-            gemm_delta = !ad && !c->mx && attn_bwd_takes_delta(c->S);
+            // where this product has no adapter branch (the 4-wave kernel, or the MXFP8 one) and the fused attention
+            // backward follows, the epilogue also forms delta = rowsum(dO * O) per head, [T, H]
+            gemm_delta = !ad && attn_bwd_takes_delta(c->S);
             if (gemm_delta) {
                 a.dl_o = at<bf16>(c, b.o); a.dl_lo = at<bf16>(c, b.o_lo); a.dl_out = at<float>(c, c->t_delta);
             }

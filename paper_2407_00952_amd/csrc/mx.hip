@@ -140,6 +140,7 @@ struct MxArgs {
     int K2, ldt;
     // epilogue (meaning as in GemmArgs)
     void *out0; void *out1; const void *aux; int ldo;
+    const bf16 *dl_o, *dl_lo; float *dl_out;   // EPI_STORE_DELTA (meaning as in GemmArgs)
     unsigned char *oq, *os;          // optional MXFP8 copy of the epilogue's bf16 tensor (see GemmArgs)
     static constexpr bool kEmitCodes = true;
 };
@@ -467,6 +468,10 @@ int launch_gemm_mx(const MxArgs &a, hipStream_t st, bool w4 = false, int epi = E
         case EPI_RESID: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_RESID>), grid, block, 0, st, a); break;
         case EPI_GELU: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_GELU>), grid, block, 0, st, a); break;
         case EPI_DGELU: hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_DGELU>), grid, block, 0, st, a); break;
+        case EPI_STORE_DELTA:
+            if (!a.dl_o || !a.dl_lo || !a.dl_out || !a.out0 || (a.N % 64) || a.nseg != 1) return SL_EINVAL;
+            hipLaunchKernelGGL((gemm_mx_kernel<false, EPI_STORE_DELTA>), grid, block, 0, st, a);
+            break;
         default: return SL_EINVAL;
         }
     }
@@ -487,6 +492,7 @@ MxArgs mx_plain(const void *xq, const void *xs, const void *wq, const void *ws, 
     for (int i = 0; i < 3; ++i) { a.zs[i] = nullptr; a.tmat[i] = nullptr; }
     a.K2 = 16; a.ldt = 32;
     a.out0 = y; a.out1 = nullptr; a.aux = nullptr; a.ldo = N;
+    a.dl_o = nullptr; a.dl_lo = nullptr; a.dl_out = nullptr;
     a.oq = nullptr; a.os = nullptr;
     return a;
 }
@@ -570,6 +576,10 @@ int launch_gemm_mx_stack(const GemmArgs &g, int epi, int nz, hipStream_t st)
     MxArgs a = mx_plain(m.xq, m.xs, m.wq, m.ws, g.bias, g.out0, g.M, g.N, g.K);
     a.nseg = g.nseg; a.seg_n = g.seg_n;
     a.out1 = g.out1; a.aux = g.aux; a.ldo = g.ldo;
+    if (epi == EPI_STORE_DELTA) {
+        if (nz != 0) return SL_EINVAL;
+        a.dl_o = g.dl_o; a.dl_lo = g.dl_lo; a.dl_out = g.dl_out;
+    }
     if (g.oq) {
         if (!g.os || (g.ldo % 32) || (g.seg_n % 32) || (epi != EPI_GELU && epi != EPI_DGELU)) return SL_EINVAL;
         a.oq = g.oq; a.os = g.os;
